@@ -1,0 +1,213 @@
+"""CPU oracle for the entropy-pruned transformer block (TEST INFRASTRUCTURE ONLY).
+
+A plain, slow, float64 NumPy statement of what the hot path computes, written
+from the paper's definitions.  It shares no code with the HIP path and must
+never be imported by the product package: only tests, the smoke check and the
+benchmark's cpu_baseline leg may call it.
+
+What each function follows:
+  entropy, mean_entropy   -- token predictive entropy (Sec. 3.3, "Adaptive
+                             Acceleration Activation", the entropy equation and
+                             the scale-mean equation); natural logarithm.
+  select                  -- "pruning low-entropy tokens according to the token
+                             reduction ratio" (Sec. 3.3, Dual-Linkage Acceleration,
+                             last sentence) / "maintaining highest-entropy tokens"
+                             (Sec. 3.2): the k largest entropies are kept.
+  pruned_block            -- Layer_j applied to the kept tokens only (Sec. 3.3,
+                             Residual Cache Reuse, first equation).  The paper
+                             leaves Layer_j opaque; the block computed here is this
+                             build's definition (pre-norm, affine-free LayerNorm,
+                             eps 1e-6, erf GELU, softmax scale 1/sqrt(dh), biases).
+                             Beyond the special cases tested (k = N equals a dense
+                             block, permutation equivariance, degenerate weights,
+                             library second opinions) its parity is unpinned
+                             against the paper.
+  bilinear_upsample,
+  merge_cache             -- Cache_{t,j} = R_out - R_in, its interpolation to the
+                             next grid and the reuse rule for pruned tokens (Sec. 3.3,
+                             Residual Cache Reuse, second and third equations).
+
+Readings taken where the paper is silent are listed in the repository's design
+notes; the ones that matter here: ties in entropy keep the lower index; NaN
+entropies rank below every number; the cache after a pruned scale is
+out - in at every position; interpolation is bilinear with half-pixel centres.
+"""
+from __future__ import annotations
+
+import numpy as np
+from scipy.special import erf
+
+LN_EPS = 1e-6
+
+
+# ----------------------------------------------------------------------------
+# entropy
+# ----------------------------------------------------------------------------
+def entropy(logits: np.ndarray) -> np.ndarray:
+    """H_i = -sum_v p_i(v) ln p_i(v), p_i = softmax(logits_i); any leading shape, last axis V."""
+    x = np.asarray(logits, dtype=np.float64)
+    m = np.max(x, axis=-1, keepdims=True)
+    e = np.exp(x - m)
+    Z = np.sum(e, axis=-1, keepdims=True)
+    p = e / Z
+    # p ln p -> 0 as p -> 0
+    with np.errstate(divide="ignore", invalid="ignore"):
+        plogp = np.where(p > 0.0, p * np.log(p), 0.0)
+    return -np.sum(plogp, axis=-1)
+
+
+def mean_entropy(H: np.ndarray) -> np.ndarray:
+    """Scale mean entropy: arithmetic mean over the N tokens of each batch row."""
+    H = np.asarray(H, dtype=np.float64)
+    return np.sum(H, axis=-1) / H.shape[-1]
+
+
+# ----------------------------------------------------------------------------
+# selection
+# ----------------------------------------------------------------------------
+def select(H32: np.ndarray, k) -> tuple[np.ndarray, np.ndarray]:
+    """Keep the k highest-entropy tokens of every batch row.
+
+    H32: [B, N] float32 entropies (compared as float32 numbers, -0 == +0).
+    k: int or length-B sequence.  Order: entropy descending, then index
+    ascending; NaN ranks below every number.  Returns (idx [B, kmax] int32,
+    ascending, unused tail = -1; mask [B, N] uint8).
+    """
+    H32 = np.asarray(H32, dtype=np.float32)
+    B, N = H32.shape
+    ks = np.full(B, k, dtype=np.int64) if np.isscalar(k) else np.asarray(k, dtype=np.int64)
+    assert ks.shape == (B,) and np.all(ks >= 0) and np.all(ks <= N)
+    kmax = int(ks.max()) if B else 0
+    idx = np.full((B, kmax), -1, dtype=np.int32)
+    mask = np.zeros((B, N), dtype=np.uint8)
+    index = np.arange(N)
+    for b in range(B):
+        h = H32[b]
+        isnan = np.isnan(h)
+        neg = np.where(isnan, 0.0, -h.astype(np.float64))
+        # lexsort: last key is primary.  NaNs last, then larger entropy first, then lower index.
+        order = np.lexsort((index, neg, isnan))
+        kept = np.sort(order[: ks[b]])
+        idx[b, : ks[b]] = kept
+        mask[b, kept] = 1
+    return idx, mask
+
+
+# ----------------------------------------------------------------------------
+# the block
+# ----------------------------------------------------------------------------
+def layer_norm(x: np.ndarray) -> np.ndarray:
+    """LayerNorm over the last axis, no affine, biased variance, eps = 1e-6."""
+    mu = np.mean(x, axis=-1, keepdims=True)
+    var = np.mean((x - mu) ** 2, axis=-1, keepdims=True)
+    return (x - mu) / np.sqrt(var + LN_EPS)
+
+
+def gelu(x: np.ndarray) -> np.ndarray:
+    """Exact (erf) GELU."""
+    return 0.5 * x * (1.0 + erf(x / np.sqrt(2.0)))
+
+
+def softmax(s: np.ndarray) -> np.ndarray:
+    m = np.max(s, axis=-1, keepdims=True)
+    e = np.exp(s - m)
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def _f64(a):
+    return None if a is None else np.asarray(a, dtype=np.float64)
+
+
+def pruned_block(x, idx, weights, k_prior, v_prior, heads):
+    """One transformer block on the kept tokens only.
+
+    x        [B, N, C]   block input (all tokens of the current scale)
+    idx      [B, k]      kept token indices per batch row
+    weights  dict: w_qkv [3C, C], b_qkv [3C], w_o [C, C], b_o [C], w_fc1 [F, C],
+             b_fc1 [F], w_fc2 [C, F], b_fc2 [C]  (out-feature major; biases may be None)
+    k_prior, v_prior [B, P, C]  keys / values of all prior scales
+    Returns y_kept [B, k, C], k_new [B, k, C], v_new [B, k, C] (the rows appended
+    to the caches at positions P .. P+k-1, in the order of idx).
+    """
+    x = _f64(x)
+    idx = np.asarray(idx, dtype=np.int64)
+    W = {n: _f64(a) for n, a in weights.items()}
+    k_prior, v_prior = _f64(k_prior), _f64(v_prior)
+    B, N, C = x.shape
+    k = idx.shape[1]
+    dh = C // heads
+    assert dh * heads == C
+
+    def bias(name):
+        b = W.get(name)
+        return 0.0 if b is None else b
+
+    y_kept = np.zeros((B, k, C))
+    k_new = np.zeros((B, k, C))
+    v_new = np.zeros((B, k, C))
+    for b in range(B):
+        xs = x[b, idx[b]]                                 # gather kept rows  [k, C]
+        u = layer_norm(xs)
+        qkv = u @ W["w_qkv"].T + bias("b_qkv")
+        q, kk, vv = qkv[:, :C], qkv[:, C:2 * C], qkv[:, 2 * C:]
+        k_new[b], v_new[b] = kk, vv
+        Kc = np.concatenate([k_prior[b], kk], axis=0)     # [P + k, C]
+        Vc = np.concatenate([v_prior[b], vv], axis=0)
+        a = np.zeros((k, C))
+        for h in range(heads):
+            sl = slice(h * dh, (h + 1) * dh)
+            scores = (q[:, sl] @ Kc[:, sl].T) / np.sqrt(dh)   # [k, P + k], no mask inside the step
+            a[:, sl] = softmax(scores) @ Vc[:, sl]
+        x1 = xs + a @ W["w_o"].T + bias("b_o")
+        hdn = gelu(layer_norm(x1) @ W["w_fc1"].T + bias("b_fc1"))
+        y_kept[b] = x1 + hdn @ W["w_fc2"].T + bias("b_fc2")
+    return y_kept, k_new, v_new
+
+
+# ----------------------------------------------------------------------------
+# residual cache reuse
+# ----------------------------------------------------------------------------
+def _axis_taps(n_in: int, n_out: int):
+    """Half-pixel-centre linear interpolation taps along one axis."""
+    dst = np.arange(n_out, dtype=np.float64)
+    src = (dst + 0.5) * (n_in / n_out) - 0.5
+    src = np.maximum(src, 0.0)
+    i0 = np.minimum(np.floor(src).astype(np.int64), n_in - 1)
+    i1 = np.minimum(i0 + 1, n_in - 1)
+    w1 = src - i0
+    return i0, i1, w1
+
+
+def bilinear_upsample(cache_prev, hp: int, wp: int, h: int, w: int) -> np.ndarray:
+    """[B, hp*wp, C] on the prior grid -> [B, h*w, C] on the current grid."""
+    c = _f64(cache_prev)
+    B, _, C = c.shape
+    c = c.reshape(B, hp, wp, C)
+    y0, y1, wy = _axis_taps(hp, h)
+    x0, x1, wx = _axis_taps(wp, w)
+    rows = c[:, y0] * (1.0 - wy)[None, :, None, None] + c[:, y1] * wy[None, :, None, None]   # [B, h, wp, C]
+    out = rows[:, :, x0] * (1.0 - wx)[None, None, :, None] + rows[:, :, x1] * wx[None, None, :, None]
+    return out.reshape(B, h * w, C)
+
+
+def merge_cache(x, y_kept, idx, cache_prev, hp, wp, h, w):
+    """Scatter kept outputs back; pruned rows reuse the upsampled residual cache.
+
+    out[b, i]       = y_kept[b, s]               if i == idx[b, s]
+                    = x[b, i] + cache_up[b, i]   otherwise
+    cache_new[b, i] = out[b, i] - x[b, i]
+    cache_prev may be None when every token is kept.
+    """
+    x, y_kept = _f64(x), _f64(y_kept)
+    idx = np.asarray(idx, dtype=np.int64)
+    B, N, C = x.shape
+    assert N == h * w
+    k = idx.shape[1]
+    if k < N:
+        out = x + bilinear_upsample(cache_prev, hp, wp, h, w)
+    else:
+        out = np.zeros_like(x)
+    for b in range(B):
+        out[b, idx[b]] = y_kept[b]
+    cache_new = out - x
+    return out, cache_new

@@ -1,0 +1,272 @@
+"""Pins for the oracle's pruned block and residual-cache merge (CPU only).
+
+The paper leaves Layer_j opaque (Sec. 3.3, Residual Cache Reuse, first
+equation), so the block is pinned to what its stated structure fixes: keeping
+every token equals an independently written dense block, per-token results do
+not depend on the order of the kept list, degenerate weights give closed forms,
+and each step agrees with a float64 library routine.  The merge is pinned to
+the cache equations (same paragraph, second and third equations) and to closed
+forms of half-pixel bilinear interpolation.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import nova_oracle as O
+
+
+def _rand_block(rng, B=2, N=7, C=8, heads=2, P=3, Fm=4, bias=True):
+    x = rng.standard_normal((B, N, C))
+    W = {
+        "w_qkv": rng.standard_normal((3 * C, C)) * 0.3, "b_qkv": rng.standard_normal(3 * C) * 0.1,
+        "w_o": rng.standard_normal((C, C)) * 0.3, "b_o": rng.standard_normal(C) * 0.1,
+        "w_fc1": rng.standard_normal((Fm * C, C)) * 0.3, "b_fc1": rng.standard_normal(Fm * C) * 0.1,
+        "w_fc2": rng.standard_normal((C, Fm * C)) * 0.3, "b_fc2": rng.standard_normal(C) * 0.1,
+    }
+    if not bias:
+        for n in ("b_qkv", "b_o", "b_fc1", "b_fc2"):
+            W[n] = None
+    kp = rng.standard_normal((B, P, C))
+    vp = rng.standard_normal((B, P, C))
+    return x, W, kp, vp
+
+
+# ---- an independent dense block, scalar python loops, token by token --------
+def _ln_scalar(v):
+    n = len(v)
+    mu = sum(v) / n
+    var = sum((a - mu) ** 2 for a in v) / n
+    return [(a - mu) / math.sqrt(var + 1e-6) for a in v]
+
+
+def _linear_scalar(v, W, b):
+    return [sum(W[o][i] * v[i] for i in range(len(v))) + (0.0 if b is None else b[o]) for o in range(len(W))]
+
+
+def _dense_block_scalar(x, W, kp, vp, heads):
+    """All N tokens of one batch row attend to P prior rows plus all N current rows."""
+    N, C = len(x), len(x[0])
+    dh = C // heads
+    qkv = [_linear_scalar(_ln_scalar(x[i]), W["w_qkv"], W["b_qkv"]) for i in range(N)]
+    keys = [list(r) for r in kp] + [r[C:2 * C] for r in qkv]
+    vals = [list(r) for r in vp] + [r[2 * C:] for r in qkv]
+    out = []
+    for i in range(N):
+        a = [0.0] * C
+        for h in range(heads):
+            q = qkv[i][h * dh:(h + 1) * dh]
+            s = [sum(q[d] * kr[h * dh + d] for d in range(dh)) / math.sqrt(dh) for kr in keys]
+            m = max(s)
+            e = [math.exp(v - m) for v in s]
+            Z = sum(e)
+            for d in range(dh):
+                a[h * dh + d] = sum(e[j] / Z * vals[j][h * dh + d] for j in range(len(keys)))
+        o = _linear_scalar(a, W["w_o"], W["b_o"])
+        x1 = [x[i][c] + o[c] for c in range(C)]
+        hid = _linear_scalar(_ln_scalar(x1), W["w_fc1"], W["b_fc1"])
+        hid = [0.5 * t * (1.0 + math.erf(t / math.sqrt(2.0))) for t in hid]
+        f = _linear_scalar(hid, W["w_fc2"], W["b_fc2"])
+        out.append([x1[c] + f[c] for c in range(C)])
+    return out, [r[C:2 * C] for r in qkv], [r[2 * C:] for r in qkv]
+
+
+@pytest.mark.parametrize("bias", [True, False])
+def test_keep_all_equals_dense_block(bias):
+    rng = np.random.default_rng(0)
+    x, W, kp, vp = _rand_block(rng, bias=bias)
+    B, N, C = x.shape
+    idx = np.tile(np.arange(N), (B, 1))
+    y, kn, vn = O.pruned_block(x, idx, W, kp, vp, heads=2)
+    Wl = {n: (None if a is None else a.tolist()) for n, a in W.items()}
+    for b in range(B):
+        ref, rk, rv = _dense_block_scalar(x[b].tolist(), Wl, kp[b].tolist(), vp[b].tolist(), 2)
+        np.testing.assert_allclose(y[b], np.array(ref), rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(kn[b], np.array(rk), rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(vn[b], np.array(rv), rtol=1e-10, atol=1e-12)
+
+
+def test_pruned_block_matches_scalar_block_on_the_subset():
+    """Kept tokens see only prior rows + kept rows: equal to the dense scalar
+    block run on the gathered sub-sequence."""
+    rng = np.random.default_rng(1)
+    x, W, kp, vp = _rand_block(rng, B=1, N=9)
+    idx = np.array([[1, 4, 5, 8]])
+    y, _, _ = O.pruned_block(x, idx, W, kp, vp, heads=2)
+    Wl = {n: a.tolist() for n, a in W.items()}
+    ref, _, _ = _dense_block_scalar(x[0, idx[0]].tolist(), Wl, kp[0].tolist(), vp[0].tolist(), 2)
+    np.testing.assert_allclose(y[0], np.array(ref), rtol=1e-10, atol=1e-12)
+
+
+def test_kept_order_does_not_change_per_token_outputs():
+    rng = np.random.default_rng(2)
+    x, W, kp, vp = _rand_block(rng, B=1, N=10)
+    idx = np.array([[0, 3, 4, 7, 9]])
+    perm = np.array([3, 0, 4, 2, 1])
+    y0, k0, v0 = O.pruned_block(x, idx, W, kp, vp, heads=2)
+    y1, k1, v1 = O.pruned_block(x, idx[:, perm], W, kp, vp, heads=2)
+    np.testing.assert_allclose(y1, y0[:, perm], rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(k1, k0[:, perm], rtol=1e-12)
+    np.testing.assert_allclose(v1, v0[:, perm], rtol=1e-12)
+
+
+def test_library_second_opinion_torch_float64():
+    rng = np.random.default_rng(3)
+    x, W, kp, vp = _rand_block(rng, B=2, N=12, C=16, heads=4, P=5)
+    idx = np.array([[0, 2, 3, 7, 10, 11], [1, 2, 4, 5, 6, 9]])
+    y, kn, vn = O.pruned_block(x, idx, W, kp, vp, heads=4)
+    t = {n: torch.from_numpy(a) for n, a in W.items()}
+    for b in range(2):
+        xs = torch.from_numpy(x[b, idx[b]])
+        u = F.layer_norm(xs, (16,), eps=1e-6)
+        qkv = F.linear(u, t["w_qkv"], t["b_qkv"])
+        q, kk, vv = qkv.split(16, dim=-1)
+        K = torch.cat([torch.from_numpy(kp[b]), kk])
+        V = torch.cat([torch.from_numpy(vp[b]), vv])
+        hd = lambda a: a.reshape(a.shape[0], 4, 4).transpose(0, 1)      # [heads, rows, dh]
+        a = F.scaled_dot_product_attention(hd(q), hd(K), hd(V)).transpose(0, 1).reshape(-1, 16)
+        x1 = xs + F.linear(a, t["w_o"], t["b_o"])
+        ref = x1 + F.linear(F.gelu(F.linear(F.layer_norm(x1, (16,), eps=1e-6), t["w_fc1"], t["b_fc1"])),
+                            t["w_fc2"], t["b_fc2"])
+        np.testing.assert_allclose(y[b], ref.numpy(), rtol=1e-9, atol=1e-11)
+        np.testing.assert_allclose(kn[b], kk.numpy(), rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(vn[b], vv.numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_degenerate_weights():
+    rng = np.random.default_rng(4)
+    x, W, kp, vp = _rand_block(rng, B=1, N=6, P=4)
+    idx = np.array([[0, 2, 5]])
+    C = x.shape[-1]
+    # all-zero weights and biases: y = x on the kept rows
+    Z = {n: np.zeros_like(a) for n, a in W.items()}
+    y, _, _ = O.pruned_block(x, idx, Z, kp, vp, heads=2)
+    np.testing.assert_allclose(y[0], x[0, idx[0]], atol=0)
+    # zero query projection -> uniform attention -> mean of all value rows;
+    # zero FFN1 weight -> FFN output = GELU(b1) W2^T + b2
+    W2 = dict(W)
+    W2["w_qkv"] = W["w_qkv"].copy(); W2["w_qkv"][:C] = 0
+    W2["b_qkv"] = W["b_qkv"].copy(); W2["b_qkv"][:C] = 0
+    W2["w_fc1"] = np.zeros_like(W["w_fc1"])
+    y, kn, vn = O.pruned_block(x, idx, W2, kp, vp, heads=2)
+    vmean = np.concatenate([vp[0], vn[0]]).mean(axis=0)
+    x1 = x[0, idx[0]] + vmean @ W["w_o"].T + W["b_o"]
+    g = np.array([0.5 * t * (1 + math.erf(t / math.sqrt(2))) for t in W["b_fc1"]])
+    ref = x1 + g @ W["w_fc2"].T + W["b_fc2"]
+    np.testing.assert_allclose(y[0], ref, rtol=1e-11, atol=1e-13)
+    # constant value cache and zero value projection: attention output is that row
+    W3 = dict(W)
+    W3["w_qkv"] = W["w_qkv"].copy(); W3["w_qkv"][2 * C:] = 0
+    W3["b_qkv"] = W["b_qkv"].copy(); W3["b_qkv"][2 * C:] = 0
+    row = rng.standard_normal(C)
+    vconst = np.tile(row, (1, 4, 1))
+    W3["w_fc1"] = np.zeros_like(W["w_fc1"]); W3["b_fc1"] = np.zeros_like(W["b_fc1"])
+    W3["b_fc2"] = np.zeros_like(W["b_fc2"])
+    # the appended value rows are 0 and the P prior rows all equal `row`
+    y, _, vn = O.pruned_block(x, idx, W3, kp, vconst, heads=2)
+    assert np.all(vn == 0)
+    a = (y[0] - x[0, idx[0]] - W["b_o"]) @ np.linalg.inv(W["w_o"].T)     # recover attention output
+    # each head's output is t * row (0 < t < 1): a convex mix of `row` and the zero rows
+    for h in range(2):
+        sl = slice(h * 4, (h + 1) * 4)
+        t = a[:, sl] / row[sl]
+        assert np.allclose(t, t[:, :1], rtol=1e-8)
+        assert np.all(t > 0) and np.all(t < 1)
+
+
+def test_layer_norm_and_gelu_special_values():
+    assert np.allclose(O.layer_norm(np.full((2, 5), 3.7)), 0.0)
+    v = np.array([[1.0, 2.0, 3.0, 4.0]])
+    ln = O.layer_norm(v)
+    assert abs(ln.mean()) < 1e-15 and ln.var() == pytest.approx(1.25 / (1.25 + 1e-6), rel=1e-12)
+    assert O.gelu(np.array([0.0]))[0] == 0.0
+    assert O.gelu(np.array([1.0]))[0] == pytest.approx(0.8413447460685429, rel=1e-14)   # Phi(1)
+    assert O.gelu(np.array([-1.0]))[0] == pytest.approx(-0.15865525393145707, rel=1e-13)
+
+
+# ----------------------------------------------------------------------------
+# residual cache reuse
+# ----------------------------------------------------------------------------
+def test_upsample_identity_constant_and_1x1():
+    rng = np.random.default_rng(5)
+    c = rng.standard_normal((2, 12, 3))
+    np.testing.assert_allclose(O.bilinear_upsample(c, 3, 4, 3, 4), c, atol=1e-15)
+    const = np.full((1, 6, 2), 2.5)
+    np.testing.assert_allclose(O.bilinear_upsample(const, 2, 3, 5, 7), 2.5, atol=1e-15)
+    one = rng.standard_normal((1, 1, 4))
+    up = O.bilinear_upsample(one, 1, 1, 3, 3)
+    np.testing.assert_allclose(up, np.tile(one, (1, 9, 1)), atol=0)
+
+
+def test_upsample_1d_closed_form_2_to_4():
+    a, b = 1.0, 5.0
+    row = np.array([a, b]).reshape(1, 2, 1)
+    up = O.bilinear_upsample(row, 1, 2, 1, 4).ravel()
+    np.testing.assert_allclose(up, [a, 0.75 * a + 0.25 * b, 0.25 * a + 0.75 * b, b], rtol=1e-15)
+    col = O.bilinear_upsample(row, 2, 1, 4, 1).ravel()
+    np.testing.assert_allclose(col, up, rtol=1e-15)
+
+
+def test_upsample_linear_ramp_interior_and_transpose_symmetry():
+    hp, wp, h, w = 13, 13, 16, 16
+    yy, xx = np.meshgrid(np.arange(hp), np.arange(wp), indexing="ij")
+    ramp = (2.0 * yy - 3.0 * xx + 1.0).reshape(1, hp * wp, 1)
+    up = O.bilinear_upsample(ramp, hp, wp, h, w).reshape(h, w)
+    sy = (np.arange(h) + 0.5) * hp / h - 0.5
+    sx = (np.arange(w) + 0.5) * wp / w - 0.5
+    inside_y = (sy >= 0) & (sy <= hp - 1)
+    inside_x = (sx >= 0) & (sx <= wp - 1)
+    ref = 2.0 * sy[:, None] - 3.0 * sx[None, :] + 1.0
+    sel = np.ix_(inside_y, inside_x)
+    np.testing.assert_allclose(up[sel], ref[sel], rtol=1e-12, atol=1e-12)
+    # interpolating the transposed field gives the transposed result (rows/columns are treated alike)
+    rng = np.random.default_rng(6)
+    c = rng.standard_normal((hp, wp))
+    a = O.bilinear_upsample(c.reshape(1, -1, 1), hp, wp, h, w).reshape(h, w)
+    bt = O.bilinear_upsample(c.T.reshape(1, -1, 1), wp, hp, w, h).reshape(w, h)
+    np.testing.assert_allclose(a, bt.T, rtol=1e-13, atol=1e-15)
+
+
+@pytest.mark.parametrize("hp,wp,h,w", [(13, 13, 16, 16), (3, 5, 7, 6), (48, 48, 64, 64), (5, 5, 4, 4)])
+def test_upsample_library_second_opinion(hp, wp, h, w):
+    rng = np.random.default_rng(7)
+    c = rng.standard_normal((2, hp * wp, 3))
+    up = O.bilinear_upsample(c, hp, wp, h, w)
+    t = torch.from_numpy(c).reshape(2, hp, wp, 3).permute(0, 3, 1, 2)
+    ref = F.interpolate(t, size=(h, w), mode="bilinear", align_corners=False, antialias=False)
+    np.testing.assert_allclose(up, ref.permute(0, 2, 3, 1).reshape(2, h * w, 3).numpy(), rtol=1e-12, atol=1e-13)
+
+
+def test_merge_rules():
+    rng = np.random.default_rng(8)
+    B, hp, wp, h, w, C = 2, 3, 3, 4, 4, 5
+    N = h * w
+    x = rng.standard_normal((B, N, C))
+    cache_prev = rng.standard_normal((B, hp * wp, C))
+    idx = np.array([[0, 5, 6, 15], [2, 3, 9, 10]])
+    y = rng.standard_normal((B, 4, C))
+    out, cn = O.merge_cache(x, y, idx, cache_prev, hp, wp, h, w)
+    up = O.bilinear_upsample(cache_prev, hp, wp, h, w)
+    for b in range(B):
+        kept = set(idx[b].tolist())
+        for i in range(N):
+            if i in kept:
+                s = idx[b].tolist().index(i)
+                assert np.array_equal(out[b, i], y[b, s])              # kept rows: the block's output, copied
+                np.testing.assert_allclose(cn[b, i], y[b, s] - x[b, i], atol=1e-15)
+            else:
+                np.testing.assert_allclose(out[b, i], x[b, i] + up[b, i], atol=1e-15)
+                np.testing.assert_allclose(cn[b, i], up[b, i], atol=1e-15)
+    np.testing.assert_allclose(cn, out - x, atol=0)
+    # nothing kept: out = x + upsampled cache everywhere
+    out0, cn0 = O.merge_cache(x, np.zeros((B, 0, C)), np.zeros((B, 0), dtype=np.int64), cache_prev, hp, wp, h, w)
+    np.testing.assert_allclose(out0, x + up, atol=0)
+    # everything kept: the prior cache is never read (NaN must not leak, None allowed)
+    allidx = np.tile(np.arange(N), (B, 1))
+    yall = rng.standard_normal((B, N, C))
+    outN, cnN = O.merge_cache(x, yall, allidx, np.full_like(cache_prev, np.nan), hp, wp, h, w)
+    assert np.array_equal(outN, yall) and not np.isnan(cnN).any()
+    outN2, _ = O.merge_cache(x, yall, allidx, None, hp, wp, h, w)
+    assert np.array_equal(outN2, yall)
