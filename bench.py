@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the NOVA hot path on one MI355X.
+
+A "step" is one next-scale step of the named workload: its L transformer blocks, each
+nova_entropy -> nova_select -> nova_pruned_block -> nova_merge_cache, enqueued back to back
+on one stream with every input (logits, weights, KV caches, residual caches) already
+resident in HBM.  Prints ONE JSON line:
+
+  value        kept tokens per second through the pruned blocks (B * sum_j k_j / step time)
+  ms_per_step  milliseconds per last-scale step
+  roofline     the dominant kernel (attention) against the bf16 MFMA peak, timed with HIP
+               events on the launch stream inside the timed region
+  kernels      per-stage device time from a second, fully instrumented pass (entropy / merge
+               as HBM GB/s, GEMMs / attention as TFLOP/s)
+  cpu_baseline the CPU oracle timed on this machine's host cores on a bounded sample
+
+Synthetic data: block 0 comes from the seeded host generators (the oracle sees the same
+bytes); the other blocks are drawn on the device with the same distributions.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+METRIC = "pruned-block kept tokens/sec + ms per last-scale step; entropy/select HBM GB/s"
+
+
+def device_block(wl, scale, j, k, gen, dtype, cap, host_block=None):
+    """Device tensors of block j.  With host_block the seeded host tensors are uploaded."""
+    import torch
+    from paper_2602_01345_amd import pack_k_cache, pack_v_cache
+    from paper_2602_01345_amd.step import BlockState
+    dev = "cuda"
+    B, N, C, H, dh, V, F = wl.B, scale.N, wl.C, wl.heads, wl.dh, wl.V, wl.F
+    P = scale.kv_len
+    if host_block is not None:
+        hb = host_block
+        return BlockState(k=k, logits=hb.logits.to(dev), weights={n: t.to(dev) for n, t in hb.weights.items()},
+                          k_cache=pack_k_cache(hb.k_prior.to(dev), H, cap), v_cache=pack_v_cache(hb.v_prior.to(dev), H, cap),
+                          cache_prev=hb.cache_prev.to(dev))
+
+    def randn(shape, std=1.0):
+        t = torch.randn(shape, generator=gen, device=dev, dtype=torch.float32)
+        if std != 1.0:
+            t *= std
+        return t.to(dtype)
+
+    temp = torch.exp(torch.empty((B, N, 1), device=dev).uniform_(math.log(0.1), math.log(10.0), generator=gen))
+    logits = (torch.randn((B, N, V), generator=gen, device=dev) * temp).to(dtype)
+    shapes = {"w_qkv": (3 * C, C), "b_qkv": (3 * C,), "w_o": (C, C), "b_o": (C,),
+              "w_fc1": (F, C), "b_fc1": (F,), "w_fc2": (C, F), "b_fc2": (C,)}
+    weights = {n: randn(s, 0.02) for n, s in shapes.items()}
+    kc = randn((B, H, cap, dh))
+    vc = randn((B, H, dh, cap))
+    kc[:, :, P:] = 0
+    vc[:, :, :, P:] = 0
+    prev = randn((B, scale.prev_grid ** 2, C))
+    return BlockState(k=k, logits=logits, weights=weights, k_cache=kc, v_cache=vc, cache_prev=prev)
+
+
+def stage_work(wl, scale, k):
+    """Algorithmic bytes / flops of each stage for one block with keep count k."""
+    e = 2 if wl.dtype == "bf16" else 4
+    B, N, C, V, F = wl.B, scale.N, wl.C, wl.V, wl.F
+    M, kv = B * k, scale.kv_len + k
+    hpwp = scale.prev_grid ** 2
+    return {
+        "entropy": ("bytes", B * N * (V * e + 4)),
+        "select": ("bytes", B * (4 * N + 4 * k + N)),
+        "gather_ln": ("bytes", 2 * M * C * e),
+        "qkv": ("flops", 2 * M * C * 3 * C),
+        "attention": ("flops", 4 * B * k * kv * C),
+        "oproj": ("flops", 2 * M * C * C),
+        "ln2": ("bytes", 2 * M * C * e),
+        "ffn1": ("flops", 2 * M * C * F),
+        "ffn2": ("flops", 2 * M * C * F),
+        "merge": ("bytes", B * (N + hpwp + k) * C * e + 2 * B * N * C * e),
+    }
+
+
+def cpu_baseline(hb, wl, scale, k):
+    """Times the CPU oracle, as it stands, on batch row 0 of block 0."""
+    import numpy as np
+    from oracle import nova_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    f64 = lambda t: t[:1].to(dtype=__import__("torch").float64).numpy()
+    t0 = time.perf_counter()
+    H = O.entropy(f64(hb.logits))
+    idx, mask = O.select(H.astype(np.float32), k)
+    W = {n: t.double().numpy() for n, t in hb.weights.items()}
+    y, _, _ = O.pruned_block(f64(hb.x), idx, W, f64(hb.k_prior), f64(hb.v_prior), wl.heads)
+    O.merge_cache(f64(hb.x), y, idx, f64(hb.cache_prev), scale.prev_grid, scale.prev_grid, scale.grid, scale.grid)
+    dt = time.perf_counter() - t0
+    return {"value": k / dt, "unit": "kept tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{wl.name} block 0, batch row 0 of {wl.B} (k={k}): entropy+select+pruned block+merge "
+                      f"in float64 NumPy, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg5", help="cfg2..cfg5 (default: the largest, cfg5)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stage-pass", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as WL
+    from paper_2602_01345_amd import Nova
+    from paper_2602_01345_amd.binding import STAGES
+    from paper_2602_01345_amd.step import StepRunner
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+    wl = WL.WORKLOADS[args.config]
+    scale = wl.last
+    dtype = WL.torch_dtype(wl.dtype)
+    cap = wl.kv_capacity(scale)
+    nova = Nova(0)
+    runner = StepRunner(nova, B=wl.B, grid=scale.grid, prev_grid=scale.prev_grid, C=wl.C, heads=wl.heads,
+                        kv_len=scale.kv_len, kv_capacity=cap, dtype=dtype, ffn_mult=wl.ffn_mult)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(wl.seed)
+    ks = wl.k_table(scale)
+
+    # block 0 from the host generators (shared with the oracle), the rest drawn on the device
+    from dataclasses import dataclass
+
+    @dataclass
+    class _HB:
+        logits: object; x: object; weights: object; k_prior: object; v_prior: object; cache_prev: object
+    kp, vp = WL.make_kv_prior(wl, 0, scale)
+    hb0 = _HB(WL.make_logits(wl, 0, scale), WL.make_x(wl, scale), WL.make_weights(wl, 0), kp, vp,
+              WL.make_cache_prev(wl, 0, scale))
+    for j in range(wl.L):
+        runner.add_block(device_block(wl, scale, j, ks[j], gen, dtype, cap, hb0 if j == 0 else None))
+    x = hb0.x.cuda()
+    torch.cuda.synchronize()
+
+    dom = STAGES.index("attention")
+    for _ in range(args.warmup):
+        runner.run_step(x)
+    torch.cuda.synchronize()
+
+    nova.profile_stages([dom])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        runner.run_step(x)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    nova.profile_stages([])
+    dom_ms, dom_n = nova.profile_collect(dom)
+
+    ms_step = dt / args.steps * 1e3
+    kept = wl.B * sum(ks)
+    work = [stage_work(wl, scale, k) for k in ks]
+    dom_flops = sum(w["attention"][1] for w in work) / len(work)          # per launch
+    dom_avg_s = dom_ms / max(dom_n, 1) * 1e-3
+    achieved = dom_flops / dom_avg_s / 1e12 if dom_avg_s > 0 else 0.0
+
+    kernels = {}
+    if not args.no_stage_pass:
+        nova.profile_stages(range(len(STAGES)))
+        reps = max(2, min(args.steps, 5))
+        for _ in range(reps):
+            runner.run_step(x)
+        torch.cuda.synchronize()
+        nova.profile_stages([])
+        for si, name in enumerate(STAGES):
+            ms, n = nova.profile_collect(si)
+            if n == 0:
+                continue
+            kind, _ = work[0][name]
+            total = sum(w[name][1] for w in work) * reps
+            rate = total / (ms * 1e-3)
+            ent = {"ms_per_step": ms / reps, "launches_per_step": n // reps}
+            if kind == "bytes":
+                ent["GB/s"] = rate / 1e9
+                ent["frac_hbm_peak"] = rate / 1e9 / HBM_PEAK_GBS
+            else:
+                ent["TFLOP/s"] = rate / 1e12
+                ent["frac_mfma_peak"] = rate / 1e12 / MFMA_BF16_PEAK_TFLOPS
+            kernels[name] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in ent.items()}
+
+    out = {
+        "metric": METRIC, "value": kept / (ms_step * 1e-3), "unit": "kept tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: last scale {scale.grid}x{scale.grid}, B={wl.B}, C={wl.C}, heads={wl.heads}, "
+                               f"L={wl.L}, V={wl.V}, P={scale.kv_len}, keep {wl.keep_hi}->{wl.keep_lo}",
+                   "kept_tokens_per_step": kept, "blocks": wl.L},
+        "roofline": {"kernel": f"attention_bf16_kernel<{wl.dh}>", "bound": "mfma", "achieved": achieved,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": None, "launches": dom_n, "avg_launch_us": dom_avg_s * 1e6,
+                     "flops_per_launch": dom_flops},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(hb0, wl, scale, ks[0])
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,195 @@
+/*
+ * nova.h -- C ABI of the MI355X (gfx950) hot path of NOVA's entropy-guided token
+ * reduction for visual autoregressive (next-scale prediction) transformers.
+ *
+ * One transformer block at one next-scale step is four calls:
+ *   nova_entropy      token predictive entropy of the codebook logits
+ *   nova_select       keep the k highest-entropy tokens of every batch row
+ *   nova_pruned_block attention + FFN on the kept tokens only
+ *   nova_merge_cache  scatter back; pruned tokens reuse the upsampled residual cache
+ *
+ * Conventions (all entry points):
+ *   - Every data pointer is a DEVICE pointer unless its comment says "host".
+ *     The caller owns every buffer; the library allocates nothing, frees
+ *     nothing and never synchronises.  All work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Inputs are read-only; outputs must not alias inputs.
+ *   - Arrays are dense row-major unless a stride argument says otherwise.
+ *   - Return value: NOVA_OK (0) or a negative NOVA_ERR_* code.  Argument
+ *     errors are detected on the host before anything is launched and leave
+ *     the outputs untouched.  Nothing is printed, nothing aborts.
+ *   - A context is bound to one device; use one context per host thread.
+ */
+#ifndef NOVA_H
+#define NOVA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  NOVA_OK = 0,
+  NOVA_ERR_INVALID_ARG = -1, /* null pointer, negative size, k > N, misaligned pointer ...      */
+  NOVA_ERR_UNSUPPORTED = -2, /* valid request the kernels do not cover (dtype, head size ...)  */
+  NOVA_ERR_WORKSPACE = -3,   /* workspace smaller than nova_workspace_bytes()                   */
+  NOVA_ERR_HIP = -4          /* a HIP runtime call failed (launch error, wrong device ...)      */
+};
+
+enum { NOVA_F32 = 0, NOVA_BF16 = 1 }; /* storage type of activations / weights / logits */
+
+typedef struct nova_ctx nova_ctx;
+
+/* Shape of one pruned block call.  F = ffn_mult * C is the FFN hidden width. */
+typedef struct nova_block_shape {
+  int32_t dtype;       /* NOVA_F32 or NOVA_BF16: x, weights, caches, outputs           */
+  int32_t B;           /* batch rows (images)                                            */
+  int32_t N;           /* tokens of the current scale per batch row (h*w)                */
+  int32_t C;           /* model width                                                    */
+  int32_t heads;       /* attention heads; dh = C / heads                                */
+  int32_t ffn_mult;    /* FFN expansion (4 in every workload here)                       */
+  int32_t kv_len;      /* P: rows already in the KV cache (all prior scales)             */
+  int32_t kv_capacity; /* rows allocated per (batch row, head) in the caches, >= P + k   */
+  int32_t k;           /* kept tokens per batch row, 0 <= k <= N                         */
+} nova_block_shape;
+
+/* Block weights, device pointers, same dtype as the activations.  Matrices are
+ * stored out-feature major: W[out][in], so a projection is y = u * W^T + b.
+ * Biases may be NULL (treated as zero). */
+typedef struct nova_block_weights {
+  const void* w_qkv; /* [3C, C]  rows 0..C-1 query, C..2C-1 key, 2C..3C-1 value */
+  const void* b_qkv; /* [3C]                                                     */
+  const void* w_o;   /* [C, C]                                                   */
+  const void* b_o;   /* [C]                                                      */
+  const void* w_fc1; /* [F, C]                                                   */
+  const void* b_fc1; /* [F]                                                      */
+  const void* w_fc2; /* [C, F]                                                   */
+  const void* b_fc2; /* [C]                                                      */
+} nova_block_weights;
+
+/* Creates a context for HIP device `device_id` (queries its properties).
+ * *out is a host object owned by the caller; release with nova_destroy. */
+int nova_create(nova_ctx** out, int device_id);
+int nova_destroy(nova_ctx* ctx);
+
+/* Static description of an error code (host string, never NULL). */
+const char* nova_strerror(int code);
+
+/* Bytes of device workspace nova_pruned_block needs for `shape` (0 if k == 0 or the
+ * shape is invalid).  The workspace holds intermediates only; contents are undefined
+ * between calls. */
+size_t nova_workspace_bytes(const nova_block_shape* shape);
+
+/*
+ * Token predictive entropy (Sec. 3.3, "Adaptive Acceleration Activation", the
+ * entropy equation): for each of the batch*rows_per_batch tokens,
+ *   H = -sum_v p(v) ln p(v),  p = softmax(logits[token, 0..V-1]),  natural log,
+ * accumulated in fp32, written as fp32 (tiny negative rounding results are
+ * clamped to +0).  A row containing NaN yields NaN.
+ *   logits           [batch*rows_per_batch, V], row r starts at element
+ *                    r*row_stride_elems (row_stride_elems >= V); dtype NOVA_F32|NOVA_BF16
+ *   entropy          out [batch*rows_per_batch] fp32
+ *   mean_entropy     out [batch] fp32 or NULL: the scale mean entropy of the same
+ *                    section (mean over the rows_per_batch tokens of a batch row).
+ *                    When non-NULL it is zeroed and accumulated by this call.
+ * batch == 0 or rows_per_batch == 0 is a no-op.  V >= 1.
+ */
+int nova_entropy(nova_ctx* ctx, void* stream, const void* logits, int logits_dtype,
+                 int64_t rows_per_batch, int batch, int V, int64_t row_stride_elems,
+                 float* entropy, float* mean_entropy);
+
+/*
+ * Entropy-guided token selection (Sec. 3.3, "Dual-Linkage Acceleration", final
+ * sentence: the lowest-entropy tokens are pruned at the reduction ratio; Sec. 3.2:
+ * the highest-entropy tokens are maintained).  For each batch row the k tokens
+ * first in the order (entropy descending, index ascending) are kept; the compare
+ * is numeric on fp32 (-0 == +0) and NaN ranks below every number.
+ *   entropy    [B, N] fp32
+ *   k          kept tokens per row when k_per_row is NULL; 0 <= k <= N
+ *   k_per_row  NULL, or DEVICE int32 [B]: per-row keep counts (clamped to [0, N] on
+ *              the device); then `k` must be >= every count and is the row pitch of kept_idx
+ *   kept_idx   out int32 [B, k]: kept token indices, ascending; entries past a row's
+ *              count are set to -1
+ *   keep_mask  out uint8 [B, N]: 1 = kept, 0 = pruned
+ * N <= 65536.  B == 0 is a no-op.  The result is exact (integer compares on the
+ * float bit patterns): identical to a stable sort.
+ */
+int nova_select(nova_ctx* ctx, void* stream, const float* entropy, int B, int N, int k,
+                const int32_t* k_per_row, int32_t* kept_idx, uint8_t* keep_mask);
+
+/*
+ * One transformer block on the kept tokens only (Sec. 3.3, "Residual Cache Reuse",
+ * first equation: R_out = Layer_j(R_in), evaluated for the kept rows; Sec. 3.2: pruning
+ * reduces the attention cost).  With xs = x[b, kept_idx[b, s], :] for s = 0..k-1:
+ *   u        = LN(xs)                       LayerNorm over C, no affine, eps 1e-6
+ *   [q|kk|vv]= u W_qkv^T + b_qkv            kk, vv are appended to the caches at row P+s
+ *   a        = per head softmax(q K^T / sqrt(dh)) V over the P+k cached rows (no mask)
+ *   x1       = xs + a W_o^T + b_o
+ *   y_kept   = x1 + GELU(LN(x1) W_fc1^T + b_fc1) W_fc2^T + b_fc2      (erf GELU)
+ * The paper does not define Layer_j; this block structure is this library's.
+ *   x        [B, N, C]
+ *   kept_idx [B, k] int32, values in [0, N) (as written by nova_select)
+ *   k_cache  [B, heads, kv_capacity, dh]   keys,   row-per-key; rows [0,P) are read,
+ *                                          rows [P, P+k) are WRITTEN, others untouched
+ *   v_cache  [B, heads, dh, kv_capacity]   values, key index minor (transposed so the
+ *                                          P.V matrix-core operand is one 16-byte read);
+ *                                          columns [0,P) read, [P,P+k) WRITTEN
+ *   y_kept   out [B, k, C]
+ *   workspace  device scratch of at least nova_workspace_bytes(shape), 256-byte aligned
+ * NOVA_BF16 requires C % 64 == 0, dh in {64, 128}, kv_capacity % 64 == 0;
+ * NOVA_F32 requires dh <= 256.  k == 0 is a no-op.
+ */
+int nova_pruned_block(nova_ctx* ctx, void* stream, const nova_block_shape* shape,
+                      const nova_block_weights* weights, const void* x, const int32_t* kept_idx,
+                      void* k_cache, void* v_cache, void* y_kept, void* workspace,
+                      size_t workspace_bytes);
+
+/*
+ * Residual cache reuse (Sec. 3.3, "Residual Cache Reuse", second and third equations):
+ *   cache_up   = bilinear upsample of cache_prev from the (hp, wp) grid to (h, w),
+ *                half-pixel centres, evaluated in fp32
+ *   out[b,i]   = y_kept[b,s]              if i == kept_idx[b,s]   (copied bit for bit)
+ *              = x[b,i] + cache_up[b,i]   otherwise               (one rounding)
+ *   cache_new[b,i] = out[b,i] - x[b,i]    (for pruned rows this is cache_up itself)
+ *   x          [B, h*w, C]      block input
+ *   y_kept     [B, k, C]        nova_pruned_block output (unused if k == 0)
+ *   kept_idx   [B, k] int32 ascending, keep_mask [B, h*w] uint8 (from nova_select)
+ *   cache_prev [B, hp*wp, C]    residual cache of the prior scale; may be NULL iff k == h*w
+ *   out        [B, h*w, C]      must not alias x
+ *   cache_new  [B, h*w, C] or NULL
+ * dtype NOVA_F32 | NOVA_BF16 applies to x, y_kept, cache_prev, out, cache_new.
+ */
+int nova_merge_cache(nova_ctx* ctx, void* stream, int dtype, int B, int C, int h, int w, int hp,
+                     int wp, int k, const void* x, const void* y_kept, const int32_t* kept_idx,
+                     const uint8_t* keep_mask, const void* cache_prev, void* out, void* cache_new);
+
+/*
+ * Instrumentation (not part of the hot path): per-kernel device timing with HIP events on
+ * the caller's stream.  While a stage's bit is set in `stage_mask`, every launch of that
+ * stage by the four entry points is bracketed by a pair of events (created on the host as
+ * needed).  nova_profile_collect waits for all recorded events, returns the summed elapsed
+ * milliseconds and the launch count of `stage` (host pointers, either may be NULL) and
+ * releases that stage's events.  A mask of 0 switches timing off (the default).
+ */
+enum {
+  NOVA_STAGE_ENTROPY = 0,   /* nova_entropy kernel                                  */
+  NOVA_STAGE_SELECT = 1,    /* nova_select kernel                                   */
+  NOVA_STAGE_GATHER_LN = 2, /* nova_pruned_block: gather kept rows + LayerNorm      */
+  NOVA_STAGE_QKV = 3,       /*   QKV projection (+ cache append)                    */
+  NOVA_STAGE_ATTENTION = 4, /*   attention over prior + kept keys                   */
+  NOVA_STAGE_OPROJ = 5,     /*   output projection + residual                       */
+  NOVA_STAGE_LN2 = 6,       /*   second LayerNorm                                   */
+  NOVA_STAGE_FFN1 = 7,      /*   FFN up projection + GELU                           */
+  NOVA_STAGE_FFN2 = 8,      /*   FFN down projection + residual                     */
+  NOVA_STAGE_MERGE = 9,     /* nova_merge_cache kernel                              */
+  NOVA_STAGE_COUNT = 10
+};
+int nova_profile_stages(nova_ctx* ctx, uint32_t stage_mask);
+int nova_profile_collect(nova_ctx* ctx, int stage, double* total_ms, int64_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NOVA_H */

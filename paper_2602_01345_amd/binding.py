@@ -1,0 +1,226 @@
+"""ctypes binding of libnova.so: argument marshalling only.
+
+Every step of the hot path runs in the HIP kernels behind the C ABI declared in
+``include/nova.h``.  PyTorch is used for device memory (tensors) and the current
+stream; nothing here computes.  The method names mirror the C entry points.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Dict, Optional
+
+import torch
+
+NOVA_F32, NOVA_BF16 = 0, 1
+STAGES = ("entropy", "select", "gather_ln", "qkv", "attention", "oproj", "ln2", "ffn1", "ffn2", "merge")
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+class NovaError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what} failed: {code}")
+        self.code = code
+
+
+class _Shape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("dtype", "B", "N", "C", "heads", "ffn_mult", "kv_len", "kv_capacity", "k")]
+
+
+class _Weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("w_qkv", "b_qkv", "w_o", "b_o", "w_fc1", "b_fc1", "w_fc2", "b_fc2")]
+
+
+@dataclass
+class BlockShape:
+    dtype: int
+    B: int
+    N: int
+    C: int
+    heads: int
+    kv_len: int
+    kv_capacity: int
+    k: int
+    ffn_mult: int = 4
+
+    def c_struct(self) -> _Shape:
+        return _Shape(self.dtype, self.B, self.N, self.C, self.heads, self.ffn_mult, self.kv_len,
+                      self.kv_capacity, self.k)
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "libnova.so")
+
+
+_LIB = None
+
+
+def load_library() -> C.CDLL:
+    """Loads libnova.so from the package directory; raises if it has not been built."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2602_01345_amd.build` "
+                           "(there is no fallback path)")
+    lib = C.CDLL(path)
+    vp, i32, i64 = C.c_void_p, C.c_int, C.c_int64
+    lib.nova_create.argtypes = [C.POINTER(vp), i32]
+    lib.nova_destroy.argtypes = [vp]
+    lib.nova_strerror.argtypes = [i32]
+    lib.nova_strerror.restype = C.c_char_p
+    lib.nova_workspace_bytes.argtypes = [C.POINTER(_Shape)]
+    lib.nova_workspace_bytes.restype = C.c_size_t
+    lib.nova_entropy.argtypes = [vp, vp, vp, i32, i64, i32, i32, i64, vp, vp]
+    lib.nova_select.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp]
+    lib.nova_pruned_block.argtypes = [vp, vp, C.POINTER(_Shape), C.POINTER(_Weights), vp, vp, vp, vp, vp, vp,
+                                      C.c_size_t]
+    lib.nova_merge_cache.argtypes = [vp, vp, i32] + [i32] * 7 + [vp] * 7
+    lib.nova_profile_stages.argtypes = [vp, C.c_uint32]
+    lib.nova_profile_collect.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.nova_profile_stages.restype = i32
+    lib.nova_profile_collect.restype = i32
+    for f in (lib.nova_create, lib.nova_destroy, lib.nova_entropy, lib.nova_select, lib.nova_pruned_block,
+              lib.nova_merge_cache):
+        f.restype = i32
+    _LIB = lib
+    return lib
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return NOVA_F32
+    if t.dtype == torch.bfloat16:
+        return NOVA_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Nova:
+    """Handle on one GPU's context; methods are the four C entry points."""
+
+    def __init__(self, device: int = 0):
+        self.lib = load_library()
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the NOVA hot path has no CPU fallback")
+        h = C.c_void_p()
+        rc = self.lib.nova_create(C.byref(h), device)
+        if rc != 0:
+            raise NovaError(rc, "nova_create")
+        self.ctx = h
+        self.device = device
+
+    def __del__(self):
+        ctx = getattr(self, "ctx", None)
+        if ctx:
+            self.lib.nova_destroy(ctx)
+            self.ctx = None
+
+    def strerror(self, code: int) -> str:
+        return self.lib.nova_strerror(code).decode()
+
+    def _check(self, rc: int, what: str):
+        if rc != 0:
+            raise NovaError(rc, f"{what} ({self.strerror(rc)})")
+
+    # -- instrumentation ------------------------------------------------------------
+    def profile_stages(self, stages):
+        mask = 0
+        for st in stages:
+            mask |= 1 << int(st)
+        self._check(self.lib.nova_profile_stages(self.ctx, mask), "nova_profile_stages")
+
+    def profile_collect(self, stage: int):
+        ms, n = C.c_double(0.0), C.c_int64(0)
+        self._check(self.lib.nova_profile_collect(self.ctx, int(stage), C.byref(ms), C.byref(n)),
+                    "nova_profile_collect")
+        return ms.value, n.value
+
+    # -- nova_entropy ---------------------------------------------------------------
+    def entropy(self, logits: torch.Tensor, entropy: torch.Tensor, mean: Optional[torch.Tensor] = None):
+        """logits [B, N, V] (f32|bf16) -> entropy [B, N] f32 (and mean [B] f32)."""
+        B, N, V = logits.shape
+        rc = self.lib.nova_entropy(self.ctx, _stream(), _ptr(logits), _dtype_code(logits), N, B, V,
+                                   logits.stride(1), _ptr(entropy), _ptr(mean))
+        self._check(rc, "nova_entropy")
+
+    # -- nova_select ----------------------------------------------------------------
+    def select(self, entropy: torch.Tensor, k: int, kept_idx: torch.Tensor, keep_mask: torch.Tensor,
+               k_per_row: Optional[torch.Tensor] = None):
+        B, N = entropy.shape
+        rc = self.lib.nova_select(self.ctx, _stream(), _ptr(entropy), B, N, k, _ptr(k_per_row),
+                                  _ptr(kept_idx), _ptr(keep_mask))
+        self._check(rc, "nova_select")
+
+    # -- nova_pruned_block ----------------------------------------------------------
+    def workspace_bytes(self, shape: BlockShape) -> int:
+        s = shape.c_struct()
+        return int(self.lib.nova_workspace_bytes(C.byref(s)))
+
+    def pruned_block(self, shape: BlockShape, weights: Dict[str, Optional[torch.Tensor]], x: torch.Tensor,
+                     kept_idx: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                     y_kept: torch.Tensor, workspace: torch.Tensor):
+        s = shape.c_struct()
+        w = _Weights(*[_ptr(weights.get(n)) for n, _ in _Weights._fields_])
+        rc = self.lib.nova_pruned_block(self.ctx, _stream(), C.byref(s), C.byref(w), _ptr(x), _ptr(kept_idx),
+                                        _ptr(k_cache), _ptr(v_cache), _ptr(y_kept), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size())
+        self._check(rc, "nova_pruned_block")
+
+    # -- nova_merge_cache -----------------------------------------------------------
+    def merge_cache(self, h: int, w: int, hp: int, wp: int, k: int, x: torch.Tensor,
+                    y_kept: Optional[torch.Tensor], kept_idx: Optional[torch.Tensor], keep_mask: torch.Tensor,
+                    cache_prev: Optional[torch.Tensor], out: torch.Tensor,
+                    cache_new: Optional[torch.Tensor] = None):
+        B, _, Cc = x.shape
+        rc = self.lib.nova_merge_cache(self.ctx, _stream(), _dtype_code(x), B, Cc, h, w, hp, wp, k, _ptr(x),
+                                       _ptr(y_kept), _ptr(kept_idx), _ptr(keep_mask), _ptr(cache_prev),
+                                       _ptr(out), _ptr(cache_new))
+        self._check(rc, "nova_merge_cache")
+
+
+# ------------------------------------------------------------------------------------
+# KV-cache layout helpers (pure permutations, no arithmetic).  The library stores keys
+# as [B, heads, capacity, dh] and values key-minor as [B, heads, dh, capacity].
+# ------------------------------------------------------------------------------------
+def pack_k_cache(k_rows: torch.Tensor, heads: int, capacity: int, fill: float = 0.0) -> torch.Tensor:
+    """[B, P, C] logical key rows -> [B, heads, capacity, dh] with rows [0, P) filled."""
+    B, P, Cc = k_rows.shape
+    dh = Cc // heads
+    out = torch.full((B, heads, capacity, dh), fill, dtype=k_rows.dtype, device=k_rows.device)
+    out[:, :, :P] = k_rows.reshape(B, P, heads, dh).permute(0, 2, 1, 3)
+    return out
+
+
+def pack_v_cache(v_rows: torch.Tensor, heads: int, capacity: int, fill: float = 0.0) -> torch.Tensor:
+    """[B, P, C] logical value rows -> [B, heads, dh, capacity] with columns [0, P) filled."""
+    B, P, Cc = v_rows.shape
+    dh = Cc // heads
+    out = torch.full((B, heads, dh, capacity), fill, dtype=v_rows.dtype, device=v_rows.device)
+    out[:, :, :, :P] = v_rows.reshape(B, P, heads, dh).permute(0, 2, 3, 1)
+    return out
+
+
+def unpack_k_rows(k_cache: torch.Tensor, start: int, stop: int) -> torch.Tensor:
+    """cache rows [start, stop) back to the logical [B, stop-start, C]."""
+    B, H, _, dh = k_cache.shape
+    return k_cache[:, :, start:stop].permute(0, 2, 1, 3).reshape(B, stop - start, H * dh)
+
+
+def unpack_v_rows(v_cache: torch.Tensor, start: int, stop: int) -> torch.Tensor:
+    B, H, dh, _ = v_cache.shape
+    return v_cache[:, :, :, start:stop].permute(0, 3, 1, 2).reshape(B, stop - start, H * dh)

@@ -1,0 +1,209 @@
+// C ABI of the library (declared in include/nova.h): argument checks on the host,
+// then dispatch to the kernel launchers.  No allocation, no synchronisation.
+#include <new>
+
+#include "nova_internal.h"
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+inline size_t esize(int dtype) { return dtype == NOVA_BF16 ? 2 : 4; }
+inline bool valid_dtype(int dtype) { return dtype == NOVA_F32 || dtype == NOVA_BF16; }
+inline size_t up256(size_t v) { return (v + 255) & ~size_t(255); }
+
+int shape_error(const nova_block_shape* s) {
+  if (!s) return NOVA_ERR_INVALID_ARG;
+  if (!valid_dtype(s->dtype)) return NOVA_ERR_UNSUPPORTED;
+  if (s->B < 0 || s->N < 0 || s->C < 1 || s->heads < 1 || s->ffn_mult < 1 || s->kv_len < 0 || s->k < 0)
+    return NOVA_ERR_INVALID_ARG;
+  if (s->k > s->N) return NOVA_ERR_INVALID_ARG;
+  if (s->C % s->heads != 0) return NOVA_ERR_INVALID_ARG;
+  if ((int64_t)s->kv_len + s->k > s->kv_capacity) return NOVA_ERR_INVALID_ARG;
+  const int dh = s->C / s->heads;
+  if (s->dtype == NOVA_BF16) {
+    if (s->C % 64 != 0 || (dh != 64 && dh != 128) || s->kv_capacity % 64 != 0) return NOVA_ERR_UNSUPPORTED;
+  } else {
+    if (s->C % 4 != 0 || dh > 256) return NOVA_ERR_UNSUPPORTED;
+    // the fp32 attention keeps one score per cached key (plus the query) in 64 KiB of LDS
+    if ((int64_t)s->kv_len + s->k + dh > 16384) return NOVA_ERR_UNSUPPORTED;
+  }
+  if ((int64_t)s->B * s->k * (int64_t)s->C * s->ffn_mult > (int64_t)1 << 40) return NOVA_ERR_UNSUPPORTED;
+  return NOVA_OK;
+}
+
+int set_device(const nova_ctx* ctx) {
+  int cur = -1;
+  if (hipGetDevice(&cur) != hipSuccess) return NOVA_ERR_HIP;
+  if (cur != ctx->device && hipSetDevice(ctx->device) != hipSuccess) return NOVA_ERR_HIP;
+  return NOVA_OK;
+}
+
+}  // namespace
+
+BlockWorkspace carve_workspace(const nova_block_shape& s, void* base) {
+  const size_t M = (size_t)s.B * s.k, C = s.C, F = (size_t)s.C * s.ffn_mult, e = esize(s.dtype);
+  BlockWorkspace w;
+  char* p = static_cast<char*>(base);
+  size_t off = 0;
+  w.u = p + off;    off += up256(M * C * e);
+  w.q = p + off;    off += up256(M * C * e);
+  w.attn = p + off; off += up256(M * C * e);
+  w.x1 = p + off;   off += up256(M * C * e);
+  w.hid = p + off;  off += up256(M * F * e);
+  w.total = off;
+  return w;
+}
+
+extern "C" {
+
+int nova_create(nova_ctx** out, int device_id) {
+  if (!out) return NOVA_ERR_INVALID_ARG;
+  *out = nullptr;
+  int n = 0;
+  if (hipGetDeviceCount(&n) != hipSuccess) return NOVA_ERR_HIP;
+  if (device_id < 0 || device_id >= n) return NOVA_ERR_INVALID_ARG;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device_id) != hipSuccess) return NOVA_ERR_HIP;
+  nova_ctx* c = new (std::nothrow) nova_ctx;
+  if (!c) return NOVA_ERR_HIP;
+  c->device = device_id;
+  c->num_cus = prop.multiProcessorCount;
+  c->lds_per_block = prop.sharedMemPerBlock;
+  c->prof_mask = 0;
+  *out = c;
+  return NOVA_OK;
+}
+
+int nova_destroy(nova_ctx* ctx) {
+  if (ctx) {
+    for (ProfRecord& r : ctx->prof) {
+      (void)hipEventDestroy(r.start);
+      (void)hipEventDestroy(r.stop);
+    }
+  }
+  delete ctx;
+  return NOVA_OK;
+}
+
+int nova_profile_stages(nova_ctx* ctx, uint32_t stage_mask) {
+  if (!ctx || (stage_mask >> NOVA_STAGE_COUNT) != 0) return NOVA_ERR_INVALID_ARG;
+  ctx->prof_mask = stage_mask;
+  return NOVA_OK;
+}
+
+int nova_profile_collect(nova_ctx* ctx, int stage, double* total_ms, int64_t* launches) {
+  if (!ctx || stage < 0 || stage >= NOVA_STAGE_COUNT) return NOVA_ERR_INVALID_ARG;
+  double ms = 0.0;
+  int64_t n = 0;
+  int rc = NOVA_OK;
+  std::vector<ProfRecord> keep;
+  for (ProfRecord& r : ctx->prof) {
+    if (r.stage != stage) { keep.push_back(r); continue; }
+    float t = 0.f;
+    if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&t, r.start, r.stop) != hipSuccess)
+      rc = NOVA_ERR_HIP;
+    else { ms += t; ++n; }
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  ctx->prof.swap(keep);
+  if (total_ms) *total_ms = ms;
+  if (launches) *launches = n;
+  return rc;
+}
+
+const char* nova_strerror(int code) {
+  switch (code) {
+    case NOVA_OK: return "ok";
+    case NOVA_ERR_INVALID_ARG: return "invalid argument";
+    case NOVA_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+    case NOVA_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case NOVA_ERR_HIP: return "HIP runtime error";
+    default: return "unknown error code";
+  }
+}
+
+size_t nova_workspace_bytes(const nova_block_shape* shape) {
+  if (shape_error(shape) != NOVA_OK || shape->k == 0 || shape->B == 0) return 0;
+  return carve_workspace(*shape, nullptr).total;
+}
+
+int nova_entropy(nova_ctx* ctx, void* stream, const void* logits, int logits_dtype, int64_t rows_per_batch,
+                 int batch, int V, int64_t row_stride_elems, float* entropy, float* mean_entropy) {
+  if (!ctx) return NOVA_ERR_INVALID_ARG;
+  if (!valid_dtype(logits_dtype)) return NOVA_ERR_UNSUPPORTED;
+  if (rows_per_batch < 0 || batch < 0 || V < 1 || row_stride_elems < V) return NOVA_ERR_INVALID_ARG;
+  if (rows_per_batch == 0 || batch == 0) return NOVA_OK;
+  if (!logits || !entropy) return NOVA_ERR_INVALID_ARG;
+  if (rows_per_batch * batch > ((int64_t)1 << 31) - 8) return NOVA_ERR_UNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(logits) % esize(logits_dtype)) != 0) return NOVA_ERR_INVALID_ARG;
+  if (int rc = set_device(ctx)) return rc;
+  StageTimer timer(ctx, static_cast<hipStream_t>(stream), NOVA_STAGE_ENTROPY);
+  hipError_t e = launch_entropy(static_cast<hipStream_t>(stream), logits, logits_dtype, rows_per_batch, batch, V,
+                                row_stride_elems, entropy, mean_entropy);
+  return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
+}
+
+int nova_select(nova_ctx* ctx, void* stream, const float* entropy, int B, int N, int k, const int32_t* k_per_row,
+                int32_t* kept_idx, uint8_t* keep_mask) {
+  if (!ctx) return NOVA_ERR_INVALID_ARG;
+  if (B < 0 || N < 0 || k < 0 || k > N) return NOVA_ERR_INVALID_ARG;
+  if (N > 65536) return NOVA_ERR_UNSUPPORTED;
+  if (B == 0 || N == 0) return NOVA_OK;
+  if (!entropy || !keep_mask || (k > 0 && !kept_idx)) return NOVA_ERR_INVALID_ARG;
+  if (int rc = set_device(ctx)) return rc;
+  StageTimer timer(ctx, static_cast<hipStream_t>(stream), NOVA_STAGE_SELECT);
+  hipError_t e = launch_select(static_cast<hipStream_t>(stream), entropy, B, N, k, k_per_row, kept_idx, keep_mask);
+  return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
+}
+
+int nova_pruned_block(nova_ctx* ctx, void* stream, const nova_block_shape* shape,
+                      const nova_block_weights* weights, const void* x, const int32_t* kept_idx, void* k_cache,
+                      void* v_cache, void* y_kept, void* workspace, size_t workspace_bytes) {
+  if (!ctx || !weights) return NOVA_ERR_INVALID_ARG;
+  if (int rc = shape_error(shape)) return rc;
+  if (shape->k == 0 || shape->B == 0) return NOVA_OK;
+  if (!x || !kept_idx || !k_cache || !v_cache || !y_kept) return NOVA_ERR_INVALID_ARG;
+  if (!weights->w_qkv || !weights->w_o || !weights->w_fc1 || !weights->w_fc2) return NOVA_ERR_INVALID_ARG;
+  const void* ptrs[] = {x, k_cache, v_cache, y_kept, weights->w_qkv, weights->w_o, weights->w_fc1, weights->w_fc2};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return NOVA_ERR_INVALID_ARG;
+  const size_t need = carve_workspace(*shape, nullptr).total;
+  if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
+    return NOVA_ERR_WORKSPACE;
+  if (int rc = set_device(ctx)) return rc;
+  const BlockWorkspace ws = carve_workspace(*shape, workspace);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e;
+  if (shape->dtype == NOVA_BF16)
+    e = launch_block_bf16(ctx, st, *shape, *weights, x, kept_idx, k_cache, v_cache, y_kept, ws);
+  else
+    e = launch_block_f32(ctx, st, *shape, *weights, static_cast<const float*>(x), kept_idx,
+                         static_cast<float*>(k_cache), static_cast<float*>(v_cache), static_cast<float*>(y_kept), ws);
+  return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
+}
+
+int nova_merge_cache(nova_ctx* ctx, void* stream, int dtype, int B, int C, int h, int w, int hp, int wp, int k,
+                     const void* x, const void* y_kept, const int32_t* kept_idx, const uint8_t* keep_mask,
+                     const void* cache_prev, void* out, void* cache_new) {
+  if (!ctx) return NOVA_ERR_INVALID_ARG;
+  if (!valid_dtype(dtype)) return NOVA_ERR_UNSUPPORTED;
+  if (B < 0 || C < 1 || h < 0 || w < 0 || k < 0) return NOVA_ERR_INVALID_ARG;
+  const int64_t N = (int64_t)h * w;
+  if (k > N || N > ((int64_t)1 << 30)) return NOVA_ERR_INVALID_ARG;
+  if (B == 0 || N == 0) return NOVA_OK;
+  if (C % (16 / (int)esize(dtype)) != 0) return NOVA_ERR_UNSUPPORTED;
+  if (!x || !out || !keep_mask || out == x) return NOVA_ERR_INVALID_ARG;
+  if (k > 0 && (!y_kept || !kept_idx)) return NOVA_ERR_INVALID_ARG;
+  if (k < N && (!cache_prev || hp < 1 || wp < 1)) return NOVA_ERR_INVALID_ARG;
+  const void* ptrs[] = {x, y_kept, cache_prev, out, cache_new};
+  for (const void* p : ptrs)
+    if (p && !aligned16(p)) return NOVA_ERR_INVALID_ARG;
+  if (int rc = set_device(ctx)) return rc;
+  StageTimer timer(ctx, static_cast<hipStream_t>(stream), NOVA_STAGE_MERGE);
+  hipError_t e = launch_merge(static_cast<hipStream_t>(stream), dtype, B, C, h, w, hp, wp, k, x, y_kept, kept_idx,
+                              keep_mask, cache_prev, out, cache_new);
+  return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
+}
+
+}  // extern "C"

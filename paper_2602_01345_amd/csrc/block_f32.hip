@@ -1,0 +1,142 @@
+// fp32 path of the pruned block (Sec. 3.3, "Residual Cache Reuse", first equation,
+// evaluated on the kept rows): plain, LDS-tiled fp32 kernels for small fp32 models.
+// It exists for correctness at full fp32 precision; the matrix-core path is block_bf16.hip.
+#include "common.h"
+#include "epilogue.h"
+#include "nova_internal.h"
+
+namespace {
+
+constexpr int kTile = 16;
+
+// out[m][n] = sum_k A[m][k] * W[n][k]  (+ epilogue); A [M, K] row-major, W [Nout, K] row-major
+template <int MODE>
+__global__ __launch_bounds__(kTile* kTile) void gemm_f32_kernel(const float* __restrict__ A,
+                                                                const float* __restrict__ W, int M, int Nout,
+                                                                int K, EpiParams<float> ep) {
+  __shared__ float As[kTile][kTile + 1];
+  __shared__ float Ws[kTile][kTile + 1];
+  const int tx = threadIdx.x % kTile, ty = threadIdx.x / kTile;
+  const int row = blockIdx.y * kTile + ty;
+  const int col = blockIdx.x * kTile + tx;
+  float acc = 0.f;
+  for (int k0 = 0; k0 < K; k0 += kTile) {
+    const int ar = blockIdx.y * kTile + ty, wr = blockIdx.x * kTile + ty, kk = k0 + tx;
+    As[ty][tx] = (ar < M && kk < K) ? A[(int64_t)ar * K + kk] : 0.f;
+    Ws[ty][tx] = (wr < Nout && kk < K) ? W[(int64_t)wr * K + kk] : 0.f;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kTile; ++i) acc = fmaf(As[ty][i], Ws[tx][i], acc);
+    __syncthreads();
+  }
+  if (row < M && col < Nout) epilogue_store<float, MODE>(ep, row, col, acc);
+}
+
+// One wave per (query row m, head).  Scores of all P+k cached keys are kept in LDS.
+__global__ __launch_bounds__(NOVA_WAVE) void attention_f32_kernel(const float* __restrict__ q,
+                                                                  const float* __restrict__ kc,
+                                                                  const float* __restrict__ vc, int k, int C,
+                                                                  int heads, int dh, int cap, int kv_total,
+                                                                  float scale, float* __restrict__ out) {
+  extern __shared__ float sc[];            // [kv_total] scores, then [dh] the query
+  float* qs = sc + kv_total;
+  const int lane = threadIdx.x;
+  const int m = blockIdx.x, head = blockIdx.y;
+  const int b = m / k;
+  const int64_t bh = (int64_t)b * heads + head;
+  const float* K = kc + bh * cap * dh;
+  const float* V = vc + bh * dh * (int64_t)cap;
+  for (int d = lane; d < dh; d += NOVA_WAVE) qs[d] = q[(int64_t)m * C + head * dh + d];
+  __syncthreads();
+  float mx = -INFINITY;
+  for (int j = lane; j < kv_total; j += NOVA_WAVE) {
+    float s = 0.f;
+    for (int d = 0; d < dh; ++d) s = fmaf(qs[d], K[(int64_t)j * dh + d], s);
+    s *= scale;
+    sc[j] = s;
+    mx = fmaxf(mx, s);
+  }
+  mx = wave_max(mx);
+  float z = 0.f;
+  for (int j = lane; j < kv_total; j += NOVA_WAVE) {
+    float e = expf(sc[j] - mx);
+    sc[j] = e;
+    z += e;
+  }
+  z = wave_sum(z);
+  __syncthreads();
+  for (int d = 0; d < dh; ++d) {
+    float a = 0.f;
+    for (int j = lane; j < kv_total; j += NOVA_WAVE) a = fmaf(sc[j], V[(int64_t)d * cap + j], a);
+    a = wave_sum(a);
+    if (lane == 0) out[(int64_t)m * C + head * dh + d] = a / z;
+  }
+}
+
+template <int MODE>
+void gemm(hipStream_t st, const float* A, const float* W, int M, int Nout, int K, const EpiParams<float>& ep) {
+  dim3 grid((Nout + kTile - 1) / kTile, (M + kTile - 1) / kTile);
+  gemm_f32_kernel<MODE><<<grid, kTile * kTile, 0, st>>>(A, W, M, Nout, K, ep);
+}
+
+}  // namespace
+
+hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shape& s, const nova_block_weights& w,
+                            const float* x, const int32_t* idx, float* kc, float* vc, float* y,
+                            const BlockWorkspace& ws) {
+  const int M = s.B * s.k, C = s.C, F = s.C * s.ffn_mult, dh = s.C / s.heads;
+  float* u = reinterpret_cast<float*>(ws.u);
+  float* q = reinterpret_cast<float*>(ws.q);
+  float* attn = reinterpret_cast<float*>(ws.attn);
+  float* x1 = reinterpret_cast<float*>(ws.x1);
+  float* hid = reinterpret_cast<float*>(ws.hid);
+
+  hipError_t e;
+  {
+    StageTimer t(ctx, st, NOVA_STAGE_GATHER_LN);
+    e = launch_gather_ln(st, NOVA_F32, x, idx, M, s.k, s.N, C, u);
+  }
+  if (e != hipSuccess) return e;
+
+  EpiParams<float> ep = {};
+  ep.C = C; ep.heads = s.heads; ep.dh = dh; ep.cap = s.kv_capacity; ep.P = s.kv_len; ep.k = s.k;
+  ep.idx = idx; ep.Ntok = s.N;
+
+  ep.bias = static_cast<const float*>(w.b_qkv); ep.out = q; ep.ldo = C; ep.kc = kc; ep.vc = vc;
+  {
+    StageTimer t(ctx, st, NOVA_STAGE_QKV);
+    gemm<EPI_QKV>(st, u, static_cast<const float*>(w.w_qkv), M, 3 * C, C, ep);
+  }
+
+  const int kv_total = s.kv_len + s.k;
+  const size_t lds = (size_t)(kv_total + dh) * sizeof(float);
+  {
+    StageTimer t(ctx, st, NOVA_STAGE_ATTENTION);
+    attention_f32_kernel<<<dim3(M, s.heads), NOVA_WAVE, lds, st>>>(q, kc, vc, s.k, C, s.heads, dh, s.kv_capacity,
+                                                                   kv_total, 1.0f / sqrtf((float)dh), attn);
+  }
+
+  ep.bias = static_cast<const float*>(w.b_o); ep.out = x1; ep.ldo = C; ep.res = x;
+  {
+    StageTimer t(ctx, st, NOVA_STAGE_OPROJ);
+    gemm<EPI_ATTN_OUT>(st, attn, static_cast<const float*>(w.w_o), M, C, C, ep);
+  }
+  {
+    StageTimer t(ctx, st, NOVA_STAGE_LN2);
+    e = launch_gather_ln(st, NOVA_F32, x1, nullptr, M, s.k, s.N, C, u);
+  }
+  if (e != hipSuccess) return e;
+
+  ep.bias = static_cast<const float*>(w.b_fc1); ep.out = hid; ep.ldo = F;
+  {
+    StageTimer t(ctx, st, NOVA_STAGE_FFN1);
+    gemm<EPI_GELU>(st, u, static_cast<const float*>(w.w_fc1), M, F, C, ep);
+  }
+
+  ep.bias = static_cast<const float*>(w.b_fc2); ep.out = y; ep.ldo = C; ep.res = x1;
+  {
+    StageTimer t(ctx, st, NOVA_STAGE_FFN2);
+    gemm<EPI_RESIDUAL>(st, hid, static_cast<const float*>(w.w_fc2), M, C, F, ep);
+  }
+  return hipGetLastError();
+}

@@ -1,0 +1,175 @@
+// Token predictive entropy H = -sum_v p(v) ln p(v), p = softmax(logits)
+// (Sec. 3.3, "Adaptive Acceleration Activation", entropy equation; the optional
+// per-batch-row mean is the scale mean entropy of the same section).
+//
+// Bandwidth-bound: every logit is read from HBM exactly once.  One wave64 owns one
+// row.  A row is consumed in chunks of up to CH 16-byte vectors per lane that are all
+// issued before the first use; per chunk the wave agrees on a running maximum m, so
+// all lanes accumulate against the same m and the final combine is a plain wave sum.
+//
+// With S = sum_v e^{x_v - m} and T = sum_v (m - x_v) e^{x_v - m}:  H = ln S + T / S.
+// Both terms are non-negative, so nothing cancels.  To keep relative accuracy when H
+// is tiny (one dominant logit) the elements equal to m are counted, not summed:
+// S = cnt + R with R = sum over x_v < m, and H = log1p(R + cnt - 1) + T / (R + cnt).
+#include "common.h"
+#include "nova_internal.h"
+
+namespace {
+
+constexpr int kWavesPerBlock = 4;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kClamp = -200.0f;   // e^-200 == 0 in fp32; keeps (m - x) * e finite for x = -inf
+
+struct Row {
+  float m;        // running maximum, wave uniform (-inf before the first element)
+  float R, T;     // per-lane partial sums against m, excluding elements equal to m
+  float cS, cT;   // wave-uniform sums of elements that once equalled the maximum
+  int cnt;        // wave-uniform count of elements equal to the current m
+
+  __device__ __forceinline__ void init() { m = -INFINITY; R = T = cS = cT = 0.f; cnt = 0; }
+
+  // new wave-uniform maximum M >= every element seen so far and in the coming chunk
+  __device__ __forceinline__ void rebase(float M) {
+    if (M > m) {
+      if (m != -INFINITY) {
+        float d = m - M;                                 // < 0
+        float dc = (d < kClamp) ? kClamp : d;
+        float f = __builtin_amdgcn_exp2f(dc * kLog2e);
+        // every earlier term e^{x-m} becomes f e^{x-m}; (m-x) grows by -d
+        T = f * fmaf(-dc, R, T);
+        R = f * R;
+        float S_old = cS + (float)cnt;
+        cT = f * fmaf(-dc, S_old, cT);
+        cS = f * S_old;
+        cnt = 0;
+      }
+      m = M;
+    }
+  }
+
+  __device__ __forceinline__ void add(float x) {
+    float d = x - m;
+    d = (d < kClamp) ? kClamp : d;
+    bool is_max = (d == 0.0f);
+    float e = __builtin_amdgcn_exp2f(d * kLog2e);
+    cnt += __popcll(__ballot(is_max));
+    e = is_max ? 0.0f : e;
+    R += e;
+    T = fmaf(-d, e, T);
+  }
+
+  // lanes that must not contribute (tail) call this instead, keeping ballots uniform
+  __device__ __forceinline__ void add_masked(float x, bool valid) {
+    float d = x - m;
+    d = (d < kClamp) ? kClamp : d;
+    bool is_max = valid && (d == 0.0f);
+    float e = __builtin_amdgcn_exp2f(d * kLog2e);
+    cnt += __popcll(__ballot(is_max));
+    e = (is_max || !valid) ? 0.0f : e;
+    float t = valid ? -d : 0.0f;
+    R += e;
+    T = fmaf(t, e, T);
+  }
+
+  __device__ __forceinline__ float finish() const {
+    float Rw = wave_sum(R) + cS;
+    float Tw = wave_sum(T) + cT;
+    // S = cnt + Rw, one maximum instance split off for log1p
+    float extra = Rw + (float)(cnt - 1);
+    float H = log1pf(extra) + Tw / (1.0f + extra);
+    if (m == -INFINITY || cnt < 1) H = __builtin_nanf("");   // empty or all -inf row: undefined
+    return (H < 0.0f) ? 0.0f : H;                             // NaN passes through
+  }
+};
+
+template <typename T, int CH>
+__global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void entropy_kernel(
+    const T* __restrict__ logits, int64_t rows, int V, int64_t stride, float* __restrict__ H,
+    float* __restrict__ mean, int64_t rows_per_batch, float inv_rows, int vec_ok) {
+  using VT = Vec16<T>;
+  constexpr int VN = VT::N;
+  const int lane = threadIdx.x & (NOVA_WAVE - 1);
+  const int wave = threadIdx.x / NOVA_WAVE;
+  const int64_t row = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+  if (row >= rows) return;                       // whole wave leaves together
+  const T* p = logits + row * stride;
+
+  Row st;
+  st.init();
+
+  int done = 0;
+  if (vec_ok) {
+    const int nvec = V / VN;                     // full 16-byte vectors in the row
+    for (int v0 = 0; v0 < nvec; v0 += CH * NOVA_WAVE) {
+      VT buf[CH];
+      bool have[CH];
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        int vi = v0 + c * NOVA_WAVE + lane;
+        have[c] = vi < nvec;
+        if (have[c]) buf[c].load(p + (int64_t)vi * VN);
+      }
+      float cm = -INFINITY;
+#pragma unroll
+      for (int c = 0; c < CH; ++c)
+        if (have[c]) {
+#pragma unroll
+          for (int i = 0; i < VN; ++i) cm = fmaxf(cm, buf[c].get(i));
+        }
+      st.rebase(wave_max(cm));
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        // have[c] is false only in the last, partial sweep; keep ballots wave-wide
+        if (__all(have[c])) {
+#pragma unroll
+          for (int i = 0; i < VN; ++i) st.add(buf[c].get(i));
+        } else if (__any(have[c])) {
+#pragma unroll
+          for (int i = 0; i < VN; ++i) st.add_masked(have[c] ? buf[c].get(i) : 0.0f, have[c]);
+        }
+      }
+    }
+    done = nvec * VN;
+  }
+  // scalar tail (or the whole row when it is not 16-byte aligned)
+  for (int e0 = done; e0 < V; e0 += NOVA_WAVE) {
+    int ei = e0 + lane;
+    bool valid = ei < V;
+    float x = valid ? ld_f32(p + ei) : -INFINITY;
+    st.rebase(wave_max(x));
+    st.add_masked(valid ? x : 0.0f, valid);
+  }
+
+  float h = st.finish();
+  if (lane == 0) {
+    H[row] = h;
+    if (mean) atomicAdd(mean + row / rows_per_batch, h * inv_rows);
+  }
+}
+
+__global__ void zero_f32_kernel(float* p, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0.0f;
+}
+
+template <typename T>
+hipError_t launch_t(hipStream_t st, const T* logits, int64_t rows_per_batch, int batch, int V,
+                    int64_t stride, float* H, float* mean) {
+  const int64_t rows = rows_per_batch * batch;
+  if (mean) zero_f32_kernel<<<(batch + 255) / 256, 256, 0, st>>>(mean, batch);
+  const int vec_ok = ((reinterpret_cast<uintptr_t>(logits) & 15) == 0) &&
+                     ((stride * (int64_t)sizeof(T)) % 16 == 0);
+  const unsigned grid = (unsigned)((rows + kWavesPerBlock - 1) / kWavesPerBlock);
+  entropy_kernel<T, 8><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(
+      logits, rows, V, stride, H, mean, rows_per_batch, 1.0f / (float)rows_per_batch, vec_ok);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_entropy(hipStream_t st, const void* logits, int dtype, int64_t rows_per_batch,
+                          int batch, int V, int64_t stride, float* H, float* mean) {
+  if (dtype == NOVA_BF16)
+    return launch_t<bf16_t>(st, static_cast<const bf16_t*>(logits), rows_per_batch, batch, V, stride, H, mean);
+  return launch_t<float>(st, static_cast<const float*>(logits), rows_per_batch, batch, V, stride, H, mean);
+}

@@ -1,0 +1,55 @@
+// Fused GEMM epilogues of the pruned block: what happens to one fp32 accumulator
+// element (row = kept-token row m in [0, B*k), col = output feature) once the
+// projection y = u W^T is done.
+#pragma once
+#include "common.h"
+
+enum EpiMode {
+  EPI_QKV = 0,        // + b_qkv; split into q (workspace), key rows and value columns of the caches
+  EPI_ATTN_OUT = 1,   // x1 = x[gathered row] + acc + b_o
+  EPI_GELU = 2,       // hid = GELU(acc + b_fc1), erf form
+  EPI_RESIDUAL = 3    // y = x1 + acc + b_fc2
+};
+
+template <typename T>
+struct EpiParams {
+  const T* bias;        // [Nout] or nullptr
+  T* out;               // q | x1 | hid | y, row pitch ldo
+  int ldo;
+  // EPI_QKV
+  T* kc;                // [B, heads, cap, dh]
+  T* vc;                // [B, heads, dh, cap]
+  int C, heads, dh, cap, P, k;
+  // residual sources
+  const T* res;         // EPI_ATTN_OUT: x [B, Ntok, C] gathered through idx; EPI_RESIDUAL: x1 [M, C]
+  const int32_t* idx;   // [B, k]
+  int Ntok;
+};
+
+__device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)); }
+
+template <typename T, int MODE>
+__device__ __forceinline__ void epilogue_store(const EpiParams<T>& p, int row, int col, float acc) {
+  float v = acc + (p.bias ? (float)p.bias[col] : 0.0f);
+  if (MODE == EPI_QKV) {
+    const int sel = col / p.C;
+    const int c = col - sel * p.C;
+    if (sel == 0) {
+      p.out[(int64_t)row * p.ldo + c] = (T)v;
+    } else {
+      const int b = row / p.k, s = row - b * p.k;
+      const int head = c / p.dh, d = c - head * p.dh;
+      const int64_t bh = (int64_t)b * p.heads + head;
+      if (sel == 1) p.kc[(bh * p.cap + p.P + s) * p.dh + d] = (T)v;
+      else          p.vc[(bh * p.dh + d) * p.cap + p.P + s] = (T)v;
+    }
+  } else if (MODE == EPI_ATTN_OUT) {
+    const int b = row / p.k;
+    const int64_t srow = (int64_t)b * p.Ntok + min(max(p.idx[row], 0), p.Ntok - 1);
+    p.out[(int64_t)row * p.ldo + col] = (T)(v + (float)p.res[srow * p.C + col]);
+  } else if (MODE == EPI_GELU) {
+    p.out[(int64_t)row * p.ldo + col] = (T)gelu_erf(v);
+  } else {
+    p.out[(int64_t)row * p.ldo + col] = (T)(v + (float)p.res[(int64_t)row * p.ldo + col]);
+  }
+}

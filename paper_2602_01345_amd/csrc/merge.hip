@@ -1,0 +1,161 @@
+// Residual cache reuse (Sec. 3.3, "Residual Cache Reuse", second and third equations):
+// kept tokens take the block's output; pruned tokens take their input plus the prior
+// scale's residual cache interpolated to the current grid; the new residual cache is
+// output minus input everywhere.
+//
+// Bandwidth-bound streaming kernel.  One wave64 owns one token row of C channels and
+// moves it in 16-byte vectors; all loads of a sweep are issued before the first use.
+// The bilinear taps (half-pixel centres) are wave-uniform and evaluated in fp32.
+#include "common.h"
+#include "nova_internal.h"
+
+namespace {
+
+constexpr int kWavesPerBlock = 4;
+constexpr int kUnroll = 4;
+
+struct Taps {
+  int i0, i1;
+  float w1;
+};
+
+__device__ __forceinline__ Taps axis_taps(int dst, int n_in, int n_out) {
+  float src = ((float)dst + 0.5f) * ((float)n_in / (float)n_out) - 0.5f;
+  src = src < 0.0f ? 0.0f : src;
+  int i0 = (int)floorf(src);
+  i0 = i0 > n_in - 1 ? n_in - 1 : i0;
+  Taps t;
+  t.i0 = i0;
+  t.i1 = i0 + 1 > n_in - 1 ? n_in - 1 : i0 + 1;
+  t.w1 = src - (float)i0;
+  return t;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void merge_kernel(
+    int B, int C, int h, int w, int hp, int wp, int k, const T* __restrict__ x, const T* __restrict__ y,
+    const int32_t* __restrict__ idx, const uint8_t* __restrict__ mask, const T* __restrict__ cache_prev,
+    T* __restrict__ out, T* __restrict__ cache_new) {
+  using VT = Vec16<T>;
+  constexpr int VN = VT::N;
+  const int lane = threadIdx.x & (NOVA_WAVE - 1);
+  const int wave = threadIdx.x / NOVA_WAVE;
+  const int N = h * w;
+  const int64_t row = (int64_t)blockIdx.x * kWavesPerBlock + wave;   // b * N + i
+  if (row >= (int64_t)B * N) return;
+  const int b = (int)(row / N);
+  const int i = (int)(row - (int64_t)b * N);
+  const int nvec = C / VN;                                           // C % VN == 0 (checked by the host)
+  const T* xr = x + row * C;
+  T* outr = out + row * C;
+  T* cnr = cache_new ? cache_new + row * C : nullptr;
+
+  if (mask[row] && k > 0) {
+    // position of token i in the ascending kept list of this batch row
+    const int32_t* list = idx + (int64_t)b * k;
+    int lo = 0, hi = k - 1;
+    while (lo < hi) {
+      int mid = (lo + hi) >> 1;
+      if (list[mid] < i) lo = mid + 1; else hi = mid;
+    }
+    const T* yr = y + ((int64_t)b * k + lo) * C;
+    for (int v0 = 0; v0 < nvec; v0 += kUnroll * NOVA_WAVE) {
+      VT vy[kUnroll], vx[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        int vi = v0 + u * NOVA_WAVE + lane;
+        if (vi < nvec) { vy[u].load(yr + vi * VN); vx[u].load(xr + vi * VN); }
+      }
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        int vi = v0 + u * NOVA_WAVE + lane;
+        if (vi < nvec) {
+          vy[u].store(outr + vi * VN);
+          if (cnr) {
+            VT c;
+#pragma unroll
+            for (int e = 0; e < VN; ++e) c.set(e, vy[u].get(e) - vx[u].get(e));
+            c.store(cnr + vi * VN);
+          }
+        }
+      }
+    }
+    return;
+  }
+
+  if (!cache_prev) {
+    // no prior cache was given (legal only when every token is kept): a row the mask still
+    // marks as pruned passes through unchanged with a zero residual
+    for (int vi = lane; vi < nvec; vi += NOVA_WAVE) {
+      VT v, z;
+      v.load(xr + vi * VN);
+#pragma unroll
+      for (int e = 0; e < VN; ++e) z.set(e, 0.0f);
+      v.store(outr + vi * VN);
+      if (cnr) z.store(cnr + vi * VN);
+    }
+    return;
+  }
+  const int oy = i / w, ox = i - oy * w;
+  const Taps ty = axis_taps(oy, hp, h);
+  const Taps tx = axis_taps(ox, wp, w);
+  const T* base = cache_prev + (int64_t)b * hp * wp * C;
+  const T* c00 = base + ((int64_t)ty.i0 * wp + tx.i0) * C;
+  const T* c01 = base + ((int64_t)ty.i0 * wp + tx.i1) * C;
+  const T* c10 = base + ((int64_t)ty.i1 * wp + tx.i0) * C;
+  const T* c11 = base + ((int64_t)ty.i1 * wp + tx.i1) * C;
+  const float wy1 = ty.w1, wy0 = 1.0f - ty.w1, wx1 = tx.w1, wx0 = 1.0f - tx.w1;
+
+  for (int v0 = 0; v0 < nvec; v0 += kUnroll * NOVA_WAVE) {
+    VT vx[kUnroll], a00[kUnroll], a01[kUnroll], a10[kUnroll], a11[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      int vi = v0 + u * NOVA_WAVE + lane;
+      if (vi < nvec) {
+        vx[u].load(xr + vi * VN);
+        a00[u].load(c00 + vi * VN); a01[u].load(c01 + vi * VN);
+        a10[u].load(c10 + vi * VN); a11[u].load(c11 + vi * VN);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      int vi = v0 + u * NOVA_WAVE + lane;
+      if (vi < nvec) {
+        VT o, c;
+#pragma unroll
+        for (int e = 0; e < VN; ++e) {
+          // rows first (y), then columns (x), as separable linear interpolation
+          float top = a00[u].get(e) * wy0 + a10[u].get(e) * wy1;
+          float bot = a01[u].get(e) * wy0 + a11[u].get(e) * wy1;
+          float up = top * wx0 + bot * wx1;
+          o.set(e, vx[u].get(e) + up);
+          c.set(e, up);
+        }
+        o.store(outr + vi * VN);
+        if (cnr) c.store(cnr + vi * VN);
+      }
+    }
+  }
+}
+
+template <typename T>
+hipError_t launch_t(hipStream_t st, int B, int C, int h, int w, int hp, int wp, int k, const void* x,
+                    const void* y, const int32_t* idx, const uint8_t* mask, const void* cache_prev, void* out,
+                    void* cache_new) {
+  const int64_t rows = (int64_t)B * h * w;
+  const unsigned grid = (unsigned)((rows + kWavesPerBlock - 1) / kWavesPerBlock);
+  merge_kernel<T><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(
+      B, C, h, w, hp, wp, k, static_cast<const T*>(x), static_cast<const T*>(y), idx, mask,
+      static_cast<const T*>(cache_prev), static_cast<T*>(out), static_cast<T*>(cache_new));
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_merge(hipStream_t st, int dtype, int B, int C, int h, int w, int hp, int wp, int k,
+                        const void* x, const void* y, const int32_t* idx, const uint8_t* mask,
+                        const void* cache_prev, void* out, void* cache_new) {
+  if (dtype == NOVA_BF16)
+    return launch_t<bf16_t>(st, B, C, h, w, hp, wp, k, x, y, idx, mask, cache_prev, out, cache_new);
+  return launch_t<float>(st, B, C, h, w, hp, wp, k, x, y, idx, mask, cache_prev, out, cache_new);
+}

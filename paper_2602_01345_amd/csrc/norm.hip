@@ -1,0 +1,66 @@
+// Row gather + LayerNorm (no affine, biased variance, eps 1e-6) feeding the block's
+// two projections.  One wave64 per row; mean and variance are two separate fp32
+// passes over the row (the second and third read hit the cache), the output is
+// rounded once to the storage type.
+#include "common.h"
+#include "nova_internal.h"
+
+namespace {
+
+constexpr int kWavesPerBlock = 4;
+constexpr float kEps = 1e-6f;
+
+template <typename T>
+__global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void gather_ln_kernel(
+    const T* __restrict__ src, const int32_t* __restrict__ idx, int M, int k, int N, int C,
+    T* __restrict__ dst) {
+  using VT = Vec16<T>;
+  constexpr int VN = VT::N;
+  const int lane = threadIdx.x & (NOVA_WAVE - 1);
+  const int m = blockIdx.x * kWavesPerBlock + threadIdx.x / NOVA_WAVE;
+  if (m >= M) return;
+  int64_t srow = m;
+  if (idx) {
+    const int b = m / k;
+    const int t = min(max(idx[m], 0), N - 1);   // idx is [B, k] and m = b * k + s; clamped, never out of bounds
+    srow = (int64_t)b * N + t;
+  }
+  const T* p = src + srow * C;
+  T* q = dst + (int64_t)m * C;
+  const int nvec = C / VN;
+
+  float sum = 0.f;
+  for (int vi = lane; vi < nvec; vi += NOVA_WAVE) {
+    VT v; v.load(p + vi * VN);
+#pragma unroll
+    for (int e = 0; e < VN; ++e) sum += v.get(e);
+  }
+  const float mean = wave_sum(sum) / (float)C;
+  float sq = 0.f;
+  for (int vi = lane; vi < nvec; vi += NOVA_WAVE) {
+    VT v; v.load(p + vi * VN);
+#pragma unroll
+    for (int e = 0; e < VN; ++e) { float d = v.get(e) - mean; sq = fmaf(d, d, sq); }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)C + kEps);
+  for (int vi = lane; vi < nvec; vi += NOVA_WAVE) {
+    VT v, o; v.load(p + vi * VN);
+#pragma unroll
+    for (int e = 0; e < VN; ++e) o.set(e, (v.get(e) - mean) * rstd);
+    o.store(q + vi * VN);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_gather_ln(hipStream_t st, int dtype, const void* src, const int32_t* idx, int M, int k,
+                            int N, int C, void* dst) {
+  const unsigned grid = (unsigned)((M + kWavesPerBlock - 1) / kWavesPerBlock);
+  if (dtype == NOVA_BF16)
+    gather_ln_kernel<bf16_t><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(
+        static_cast<const bf16_t*>(src), idx, M, k, N, C, static_cast<bf16_t*>(dst));
+  else
+    gather_ln_kernel<float><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(
+        static_cast<const float*>(src), idx, M, k, N, C, static_cast<float*>(dst));
+  return hipGetLastError();
+}

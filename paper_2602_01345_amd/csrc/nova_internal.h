@@ -1,0 +1,80 @@
+// Host-side declarations shared by the C ABI (api.hip) and the kernel files.
+// Every launch_* function validates nothing: api.hip has already checked the
+// arguments against what the kernels and their grids assume.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/nova.h"
+
+#include <vector>
+
+struct ProfRecord {
+  int stage;
+  hipEvent_t start, stop;
+};
+
+struct nova_ctx {
+  int device;
+  int num_cus;
+  size_t lds_per_block;
+  uint32_t prof_mask;
+  std::vector<ProfRecord> prof;
+};
+
+// Brackets one kernel launch with a pair of events when its stage is being timed.
+struct StageTimer {
+  nova_ctx* ctx;
+  hipStream_t st;
+  hipEvent_t stop;
+  bool on;
+  StageTimer(nova_ctx* c, hipStream_t s, int stage) : ctx(c), st(s), stop(nullptr), on(false) {
+    if (!c || !((c->prof_mask >> stage) & 1u)) return;
+    hipEvent_t a = nullptr, b = nullptr;
+    if (hipEventCreate(&a) != hipSuccess) return;
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+    (void)hipEventRecord(a, s);
+    c->prof.push_back({stage, a, b});
+    stop = b;
+    on = true;
+  }
+  ~StageTimer() {
+    if (on) (void)hipEventRecord(stop, st);
+  }
+};
+
+// entropy.hip
+hipError_t launch_entropy(hipStream_t st, const void* logits, int dtype, int64_t rows_per_batch,
+                          int batch, int V, int64_t stride, float* H, float* mean);
+// select.hip
+hipError_t launch_select(hipStream_t st, const float* H, int B, int N, int k, const int32_t* k_per_row,
+                         int32_t* idx, uint8_t* mask);
+// merge.hip
+hipError_t launch_merge(hipStream_t st, int dtype, int B, int C, int h, int w, int hp, int wp, int k,
+                        const void* x, const void* y, const int32_t* idx, const uint8_t* mask,
+                        const void* cache_prev, void* out, void* cache_new);
+
+// Workspace carving for the block (element counts; every region 256-byte aligned).
+struct BlockWorkspace {
+  char* u;     // [M, C]  LayerNorm output (reused for both norms)
+  char* q;     // [M, C]  queries
+  char* attn;  // [M, C]  attention output
+  char* x1;    // [M, C]  residual stream after attention
+  char* hid;   // [M, F]  FFN hidden
+  size_t total;
+};
+BlockWorkspace carve_workspace(const nova_block_shape& s, void* base);
+
+// norm.hip: dst[m] = LayerNorm(src[row(m)]); with idx, row(m) = (m / k) * N + idx[m], else row(m) = m
+hipError_t launch_gather_ln(hipStream_t st, int dtype, const void* src, const int32_t* idx, int M, int k,
+                            int N, int C, void* dst);
+
+// block_f32.hip: plain fp32 kernels (correctness path for small fp32 models)
+hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shape& s, const nova_block_weights& w,
+                            const float* x, const int32_t* idx, float* kc, float* vc, float* y,
+                            const BlockWorkspace& ws);
+// block_bf16.hip: MFMA path
+hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_shape& s,
+                             const nova_block_weights& w, const void* x, const int32_t* idx, void* kc,
+                             void* vc, void* y, const BlockWorkspace& ws);

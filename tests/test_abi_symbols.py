@@ -1,0 +1,56 @@
+"""The built C-ABI library loads (no GPU needed) and exports every function include/nova.h declares."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "nova.h")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nova_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_four_entry_points():
+    names = _declared_functions()
+    for n in ("nova_entropy", "nova_select", "nova_pruned_block", "nova_merge_cache",
+              "nova_create", "nova_destroy", "nova_workspace_bytes", "nova_strerror"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2602_01345_amd import library_path
+    path = library_path()
+    if not os.path.exists(path):
+        pytest.fail(f"{path} not built: run `python -m paper_2602_01345_amd.build`")
+    lib = ctypes.CDLL(path)
+    for name in _declared_functions():
+        assert hasattr(lib, name), f"{name} is declared in nova.h but not exported"
+    lib.nova_strerror.restype = ctypes.c_char_p
+    assert lib.nova_strerror(0) == b"ok"
+    assert b"argument" in lib.nova_strerror(-1)
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2602_01345_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in src, f"{f} mentions the oracle"
+
+
+def test_workload_keep_tables():
+    import workloads as WL
+    w2, w5 = WL.WORKLOADS["cfg2"], WL.WORKLOADS["cfg5"]
+    assert w2.k_table()[:3] == [205, 198, 192] and w2.k_table()[-1] == 103 and sum(w2.k_table()) == 2466
+    assert w5.k_table()[0] == 2458 and w5.k_table()[-1] == 820 and sum(w5.k_table()) == 52445
+    assert sum(WL.WORKLOADS["cfg3"].k_table()) == 3855
+    assert WL.WORKLOADS["cfg4"].k_table() == [512] * 36
+    assert [s.kv_len for s in WL.WORKLOADS["cfg5"].scales] == [1497, 2521, 4121, 6425]
+    assert WL.WORKLOADS["cfg4"].last.kv_len == 1216 and WL.WORKLOADS["cfg1"].last.kv_len == 424
+    assert WL.WORKLOADS["cfg3"].scales[0].kv_len == 255

@@ -1,0 +1,259 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Tolerances: kept-index lists and masks bit-exact; fp32 entropies |dH| <= 1e-5|H| + 1e-7;
+bf16 tensors max|d|/max|ref| <= 2e-2; fp32 block tensors <= 2e-5 (fp32 accumulation over
+at most 256 terms).  Selection is always compared on the same fp32 entropy array.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as WL
+from oracle import nova_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hx():
+    import harness
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU and the built libnova.so (no fallback)")
+    return harness
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ----------------------------------------------------------------------------------
+# entropy
+# ----------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("V", [512, 4096, 1000, 513, 7, 1, 20000])
+def test_entropy_matches_oracle(hx, dtype, V):
+    _say(f"entropy dtype={dtype} V={V}")
+    wl = WL.Workload("t", dtype, B=3, C=64, heads=4, L=1, V=V, keep_hi=.5, keep_lo=.5,
+                     scales=(WL.Scale(grid=9, prev_grid=7, kv_len=10),), seed=3)
+    logits = WL.make_logits(wl, 0)                       # [3, 81, V] log-uniform temperatures
+    d = logits.cuda()
+    H = torch.empty((3, 81), dtype=torch.float32, device="cuda")
+    mean = torch.empty((3,), dtype=torch.float32, device="cuda")
+    hx.nova().entropy(d, H, mean)
+    torch.cuda.synchronize()
+    ref = O.entropy(hx.f64(logits))
+    assert hx.entropy_ok(H, ref)
+    assert np.allclose(mean.cpu().numpy(), O.mean_entropy(ref), rtol=2e-5, atol=1e-6)
+
+
+def test_entropy_closed_forms_and_edge_rows(hx):
+    _say("entropy closed forms")
+    V = 4096
+    x = torch.zeros((1, 8, V), dtype=torch.float32)
+    x[0, 0] = 3.25                                      # uniform -> ln V
+    x[0, 1] = -1e4; x[0, 1, 77] = 50.0                  # one-hot -> 0
+    x[0, 2, :16] = 3.0                                  # two-level
+    x[0, 3] = torch.linspace(-30, 30, V)
+    x[0, 4] = float("-inf"); x[0, 4, 5] = 1.0; x[0, 4, 9] = 1.0   # two survivors -> ln 2
+    x[0, 5, 100] = float("nan")                         # NaN row -> NaN
+    x[0, 6] = 1e4 + torch.randn(V, generator=torch.Generator().manual_seed(0))   # huge offset
+    x[0, 7, 0] = 20.0                                   # tiny entropy
+    H = torch.empty((1, 8), dtype=torch.float32, device="cuda")
+    hx.nova().entropy(x.cuda(), H)
+    got = H.cpu().numpy()[0]
+    assert got[0] == pytest.approx(math.log(V), rel=1e-6)
+    assert got[1] == 0.0
+    assert got[4] == pytest.approx(math.log(2.0), rel=1e-6)
+    assert math.isnan(got[5])
+    ref = O.entropy(hx.f64(x))[0]
+    ok = [0, 1, 2, 3, 4, 6, 7]
+    assert hx.entropy_ok(got[ok], ref[ok])
+    assert got[7] == pytest.approx(0.00017724744533827648, rel=1e-5)
+
+
+def test_entropy_strided_and_unaligned_rows(hx):
+    _say("entropy strided/unaligned")
+    g = torch.Generator().manual_seed(1)
+    base = (torch.randn((2, 50, 1030), generator=g) * 4).to(torch.bfloat16).cuda()
+    view = base[:, :, :1001]                            # row stride 1030, V = 1001: rows not 16-byte aligned
+    H = torch.empty((2, 50), dtype=torch.float32, device="cuda")
+    n = hx.nova()
+    rc = n.lib.nova_entropy(n.ctx, None, view.data_ptr(), 1, 50, 2, 1001, 1030, H.data_ptr(), None)
+    assert rc == 0
+    torch.cuda.synchronize()
+    assert hx.entropy_ok(H, O.entropy(hx.f64(view)))
+
+
+# ----------------------------------------------------------------------------------
+# selection
+# ----------------------------------------------------------------------------------
+def _run_select(hx, H32, k, k_per_row=None):
+    B, N = H32.shape
+    d = torch.from_numpy(H32).cuda()
+    idx = torch.full((B, max(k, 1)), -7, dtype=torch.int32, device="cuda")
+    mask = torch.full((B, N), 9, dtype=torch.uint8, device="cuda")
+    kp = None if k_per_row is None else torch.tensor(k_per_row, dtype=torch.int32, device="cuda")
+    hx.nova().select(d, k, idx, mask, kp)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), mask.cpu().numpy()
+
+
+@pytest.mark.parametrize("N", [1, 63, 169, 256, 1024, 4096, 5000, 8192, 8193, 16384, 40000])
+def test_select_bit_exact(hx, N):
+    _say(f"select N={N}")
+    rng = np.random.default_rng(N)
+    H = (rng.random((3, N)) * 8.3).astype(np.float32)
+    H[1] = np.round(H[1] * 4) / 4                      # heavy ties
+    H[2, ::7] = 0.0
+    H[2, 1::13] = -0.0
+    if N > 20:
+        H[2, 5] = np.nan
+        H[2, 11] = np.inf
+    for k in sorted({0, 1, N // 3, N // 2, N - 1, N}):
+        if k < 0:
+            continue
+        idx, mask = _run_select(hx, H, k)
+        ridx, rmask = O.select(H, k)
+        assert np.array_equal(mask, rmask), f"mask differs at k={k}"
+        assert np.array_equal(idx[:, :k], ridx[:, :k]), f"idx differs at k={k}"
+
+
+def test_select_all_equal_and_per_row_k(hx):
+    _say("select all-equal / per-row k")
+    H = np.full((4, 777), 1.5, dtype=np.float32)
+    idx, mask = _run_select(hx, H, 100)
+    assert np.array_equal(idx, np.tile(np.arange(100, dtype=np.int32), (4, 1)))
+    rng = np.random.default_rng(0)
+    H = rng.random((4, 300)).astype(np.float32)
+    ks = [0, 17, 300, 120]
+    idx, mask = _run_select(hx, H, 300, ks)
+    ridx, rmask = O.select(H, ks)
+    assert np.array_equal(mask, rmask)
+    assert np.array_equal(idx, ridx)                    # including the -1 tails
+
+
+# ----------------------------------------------------------------------------------
+# merge
+# ----------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("grids", [(13, 16), (3, 7), (16, 16), (48, 64), (5, 4)])
+def test_merge_matches_oracle(hx, dtype, grids):
+    hp, h = grids
+    _say(f"merge dtype={dtype} {hp}->{h}")
+    td = WL.torch_dtype(dtype)
+    tol = hx.BF16_TOL if dtype == "bf16" else 1e-6
+    g = torch.Generator().manual_seed(hp * 100 + h)
+    B, C, N = 2, 72 if dtype == "f32" else 136, h * h
+    x = torch.randn((B, N, C), generator=g).to(td)
+    prev = torch.randn((B, hp * hp, C), generator=g).to(td)
+    for k in sorted({0, 1, N // 2, N}):
+        H = torch.rand((B, N), generator=g).numpy()
+        idx, mask = O.select(H, k)
+        y = torch.randn((B, max(k, 1), C), generator=g).to(td)
+        out = torch.empty((B, N, C), dtype=td, device="cuda")
+        cn = torch.empty((B, N, C), dtype=td, device="cuda")
+        cache = prev.cuda() if k < N else torch.full_like(prev, float("nan")).cuda()
+        hx.nova().merge_cache(h, h, hp, hp, k, x.cuda(), y.cuda(),
+                              torch.from_numpy(idx if k else np.zeros((B, 1), np.int32)).cuda(),
+                              torch.from_numpy(mask).cuda(), cache, out, cn)
+        torch.cuda.synchronize()
+        ro, rc = O.merge_cache(hx.f64(x), hx.f64(y)[:, :k], idx[:, :k], hx.f64(prev), hp, hp, h, h)
+        assert hx.nerr(out, ro) <= tol and hx.nerr(cn, rc) <= tol
+        # kept rows are copied bit for bit
+        for b in range(B):
+            if k:
+                assert torch.equal(out[b, torch.from_numpy(idx[b, :k]).long().cuda()].cpu(), y[b, :k])
+    # no prior cache at all when every token is kept
+    hx.nova().merge_cache(h, h, hp, hp, N, x.cuda(), y.cuda(), torch.from_numpy(idx).cuda(),
+                          torch.from_numpy(mask).cuda(), None, out, None)
+    torch.cuda.synchronize()
+    assert torch.equal(out.cpu(), y)
+
+
+# ----------------------------------------------------------------------------------
+# the block, small shapes spanning several tiles with ragged tails
+# ----------------------------------------------------------------------------------
+def _custom(dtype, B, grid, prev, P, C, heads, V=64, seed=5):
+    return WL.Workload("custom", dtype, B=B, C=C, heads=heads, L=1, V=V, keep_hi=.5, keep_lo=.5,
+                       scales=(WL.Scale(grid=grid, prev_grid=prev, kv_len=P),), seed=seed)
+
+
+@pytest.mark.parametrize("C,heads", [(128, 2), (256, 2), (192, 3)])
+@pytest.mark.parametrize("k", [1, 150, 289])
+def test_block_bf16_small(hx, C, heads, k):
+    _say(f"block bf16 C={C} heads={heads} k={k}")
+    wl = _custom("bf16", B=2, grid=17, prev=13, P=100, C=C, heads=heads)
+    hb = hx.make_host_block(wl, 0, k=k)
+    errs = hx.check_block(hb, hx.BF16_TOL)
+    _say(f"   errors {errs}")
+
+
+@pytest.mark.parametrize("k", [0, 1, 37, 100])
+def test_block_f32_small(hx, k):
+    _say(f"block f32 k={k}")
+    wl = _custom("f32", B=2, grid=10, prev=7, P=45, C=48, heads=3)
+    hb = hx.make_host_block(wl, 0, k=k)
+    errs = hx.check_block(hb, hx.F32_TOL)
+    _say(f"   errors {errs}")
+
+
+def test_block_keep_zero_bf16(hx):
+    _say("block bf16 k=0")
+    wl = _custom("bf16", B=2, grid=8, prev=6, P=64, C=128, heads=2)
+    hx.check_block(hx.make_host_block(wl, 0, k=0), hx.BF16_TOL)
+
+
+# ----------------------------------------------------------------------------------
+# the five workloads (first and last block of the last scale; a subset of batch rows where
+# the oracle would take too long)
+# ----------------------------------------------------------------------------------
+def test_cfg1_full_step(hx):
+    _say("cfg1 full")
+    wl = WL.WORKLOADS["cfg1"]
+    errs = hx.check_block(hx.make_host_block(wl, 0), hx.F32_TOL)
+    _say(f"   errors {errs}")
+
+
+@pytest.mark.parametrize("name,rows", [("cfg2", None), ("cfg3", [0, 15]), ("cfg4", [3]), ("cfg5", [1])])
+@pytest.mark.parametrize("which", ["first", "last"])
+def test_workload_blocks(hx, name, rows, which):
+    wl = WL.WORKLOADS[name]
+    j = 0 if which == "first" else wl.L - 1
+    _say(f"{name} block {j} k={wl.k(j)} rows={rows}")
+    errs = hx.check_block(hx.make_host_block(wl, j), hx.BF16_TOL, rows=rows)
+    _say(f"   errors {errs}")
+
+
+def test_earlier_pruned_scales(hx):
+    """cfg3's 13x13 scale and cfg5's 32x32 scale (prior grids 10 and 24)."""
+    for name, si, rows in (("cfg3", 0, [1]), ("cfg5", 0, [0])):
+        wl = WL.WORKLOADS[name]
+        s = wl.scales[si]
+        _say(f"{name} scale {s.grid} P={s.kv_len}")
+        hx.check_block(hx.make_host_block(wl, 1, scale=s), hx.BF16_TOL, rows=rows)
+
+
+# ----------------------------------------------------------------------------------
+# argument errors are reported, not launched
+# ----------------------------------------------------------------------------------
+def test_argument_errors(hx):
+    _say("argument errors")
+    n = hx.nova()
+    H = torch.zeros((2, 16), dtype=torch.float32, device="cuda")
+    idx = torch.zeros((2, 16), dtype=torch.int32, device="cuda")
+    mask = torch.zeros((2, 16), dtype=torch.uint8, device="cuda")
+    lib = n.lib
+    assert lib.nova_select(n.ctx, None, H.data_ptr(), 2, 16, 17, None, idx.data_ptr(), mask.data_ptr()) == -1
+    assert lib.nova_select(n.ctx, None, None, 2, 16, 4, None, idx.data_ptr(), mask.data_ptr()) == -1
+    assert lib.nova_select(n.ctx, None, H.data_ptr(), 2, 70000, 4, None, idx.data_ptr(), mask.data_ptr()) == -2
+    assert lib.nova_entropy(n.ctx, None, H.data_ptr(), 0, 16, 2, 0, 0, H.data_ptr(), None) == -1
+    assert lib.nova_entropy(n.ctx, None, H.data_ptr(), 5, 16, 2, 1, 1, H.data_ptr(), None) == -2
+    from paper_2602_01345_amd import BlockShape
+    bad = BlockShape(1, 2, 16, 128, 3, 0, 64, 4)          # C % heads != 0
+    assert n.workspace_bytes(bad) == 0
+    ok = BlockShape(1, 2, 16, 128, 2, 0, 64, 4)
+    assert n.workspace_bytes(ok) > 0
+    assert n.workspace_bytes(BlockShape(1, 2, 16, 128, 2, 62, 64, 4)) == 0     # P + k > capacity
+    assert n.workspace_bytes(BlockShape(1, 2, 16, 96, 2, 0, 64, 4)) == 0       # dh = 48 unsupported in bf16
