@@ -33,11 +33,12 @@ def f64(t) -> np.ndarray:
     return np.asarray(t, dtype=np.float64)
 
 
-def nerr(got, ref) -> float:
+def nerr(got, ref, scale_ref=None) -> float:
+    """max|got - ref| / max|scale_ref| (scale_ref defaults to ref)."""
     got, ref = f64(got), f64(ref)
     assert got.shape == ref.shape, (got.shape, ref.shape)
     assert np.isfinite(got).all(), "non-finite values in the GPU result"
-    denom = np.max(np.abs(ref))
+    denom = np.max(np.abs(ref if scale_ref is None else f64(scale_ref)))
     return float(np.max(np.abs(got - ref)) / (denom if denom > 0 else 1.0))
 
 
@@ -120,7 +121,10 @@ def check_block(hb: HostBlock, tol: float, rows=None, poison: bool = True) -> Di
         errs["k_new"] = nerr(unpack_k_rows(st.k_cache, P, P + k)[rows], ref["k_new"])
         errs["v_new"] = nerr(unpack_v_rows(st.v_cache, P, P + k)[rows], ref["v_new"])
     errs["out"] = nerr(st.out[rows], ref["out"])
-    errs["cache_new"] = nerr(st.cache_new[rows], ref["cache_new"])
+    # cache_new = out - x is a difference of two stored tensors: its absolute error is that of
+    # `out`, so it is measured on the scale of `out` (on kept rows the residual itself can be
+    # far smaller than the bf16 spacing of the activations it is the difference of)
+    errs["cache_new"] = nerr(st.cache_new[rows], ref["cache_new"], scale_ref=ref["out"])
     for name, e in errs.items():
         assert e <= tol, f"{name}: normalised max error {e:.3e} > {tol:.1e}"
     # prior cache rows must be untouched
