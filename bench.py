@@ -117,6 +117,8 @@ def main():
     ap.add_argument("--config", default="cfg5", help="cfg2..cfg5 (default: the largest, cfg5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stage-pass", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (known HBM traffic) for scaling rocprofv3 byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -153,6 +155,14 @@ def main():
         runner.add_block(device_block(wl, scale, j, ks[j], gen, dtype, cap, hb0 if j == 0 else None))
     x = hb0.x.cuda()
     torch.cuda.synchronize()
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # reads 1 GiB, writes 1 GiB per launch
+        torch.cuda.synchronize()
+        del src, dst
 
     dom = STAGES.index("attention")
     for _ in range(args.warmup):
