@@ -1,5 +1,6 @@
 // C ABI of the library (declared in include/nova.h): argument checks on the host,
 // then dispatch to the kernel launchers.  No allocation, no synchronisation.
+#include <cstdlib>
 #include <new>
 
 #include "nova_internal.h"
@@ -70,6 +71,10 @@ int nova_create(nova_ctx** out, int device_id) {
   c->num_cus = prop.multiProcessorCount;
   c->lds_per_block = prop.sharedMemPerBlock;
   c->prof_mask = 0;
+  const char* g = getenv("NOVA_GEMM_CFG");
+  const char* a = getenv("NOVA_ATTN_CFG");
+  c->gemm_cfg = g ? atoi(g) : -1;
+  c->attn_cfg = a ? atoi(a) : -1;
   *out = c;
   return NOVA_OK;
 }

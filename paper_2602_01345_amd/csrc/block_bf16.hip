@@ -29,105 +29,6 @@ namespace {
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
-__device__ __forceinline__ int mfma_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
-
-// =============================== GEMM ==============================================
-constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int LDT = BK + 8;          // LDS row pitch in elements (144 B: conflict-free 16-byte reads)
-constexpr int GEMM_THREADS = 256;
-
-template <int MODE>
-__global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(const bf16_t* __restrict__ A,
-                                                                 const bf16_t* __restrict__ W, int M, int Nout,
-                                                                 int K, EpiParams<bf16_t> ep) {
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * LDT];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * LDT];
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-
-  // global -> LDS mapping: 16-byte chunk (row = tid/8 + 32*i, part = tid%8)
-  const int lrow = tid >> 3, lpart = tid & 7;
-  const bf16_t* ga[4];
-  const bf16_t* gb[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int ra = min(m0 + lrow + 32 * i, M - 1);       // rows past the edge re-read the last row; never stored
-    int rb = min(n0 + lrow + 32 * i, Nout - 1);
-    ga[i] = A + (int64_t)ra * K + lpart * 8;
-    gb[i] = W + (int64_t)rb * K + lpart * 8;
-  }
-  bf16x8 ra_[4], rb_[4];
-  auto gload = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      ra_[i] = *reinterpret_cast<const bf16x8*>(ga[i] + k0);
-      rb_[i] = *reinterpret_cast<const bf16x8*>(gb[i] + k0);
-    }
-  };
-  auto lstore = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      *reinterpret_cast<bf16x8*>(&As[buf][(lrow + 32 * i) * LDT + lpart * 8]) = ra_[i];
-      *reinterpret_cast<bf16x8*>(&Bs[buf][(lrow + 32 * i) * LDT + lpart * 8]) = rb_[i];
-    }
-  };
-
-  f32x16 acc[2][2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  const int KT = K / BK;
-  gload(0);
-  lstore(0);
-  __syncthreads();
-  const int arow = (wm * 64 + (lane & 31)) * LDT + (lane >> 5) * 8;
-  const int brow = (wn * 64 + (lane & 31)) * LDT + (lane >> 5) * 8;
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < KT) gload((kt + 1) * BK);
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 a[2], b[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const bf16x8*>(&As[buf][arow + i * 32 * LDT + ks * 16]);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const bf16x8*>(&Bs[buf][brow + j * 32 * LDT + ks * 16]);
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = mfma32(a[i], b[j], acc[i][j]);
-    }
-    if (kt + 1 < KT) lstore(buf ^ 1);
-    __syncthreads();
-  }
-
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int col = n0 + wn * 64 + j * 32 + (lane & 31);
-      if (col < Nout) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = m0 + wm * 64 + i * 32 + mfma_row(r, lane);
-          if (row < M) epilogue_store<bf16_t, MODE>(ep, row, col, acc[i][j][r]);
-        }
-      }
-    }
-}
-
-template <int MODE>
-void gemm(hipStream_t st, const bf16_t* A, const bf16_t* W, int M, int Nout, int K, const EpiParams<bf16_t>& ep) {
-  dim3 grid((Nout + BN - 1) / BN, (M + BM - 1) / BM);
-  gemm_bf16_kernel<MODE><<<grid, GEMM_THREADS, 0, st>>>(A, W, M, Nout, K, ep);
-}
 
 // =============================== attention =========================================
 constexpr int ATT_THREADS = 256;     // 4 waves, 32 queries each
@@ -323,7 +224,7 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
   ep.bias = static_cast<const bf16_t*>(w.b_qkv); ep.out = q; ep.ldo = C; ep.kc = kc; ep.vc = vc;
   {
     StageTimer t(ctx, st, NOVA_STAGE_QKV);
-    gemm<EPI_QKV>(st, u, static_cast<const bf16_t*>(w.w_qkv), M, 3 * C, C, ep);
+    e = launch_gemm_bf16(ctx, st, EPI_QKV, u, w.w_qkv, M, 3 * C, C, ep);
   }
 
   const int kv_total = s.kv_len + s.k;
@@ -342,7 +243,7 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
   ep.bias = static_cast<const bf16_t*>(w.b_o); ep.out = x1; ep.ldo = C; ep.res = x;
   {
     StageTimer t(ctx, st, NOVA_STAGE_OPROJ);
-    gemm<EPI_ATTN_OUT>(st, attn, static_cast<const bf16_t*>(w.w_o), M, C, C, ep);
+    e = launch_gemm_bf16(ctx, st, EPI_ATTN_OUT, attn, w.w_o, M, C, C, ep);
   }
   {
     StageTimer t(ctx, st, NOVA_STAGE_LN2);
@@ -353,13 +254,13 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
   ep.bias = static_cast<const bf16_t*>(w.b_fc1); ep.out = hid; ep.ldo = F;
   {
     StageTimer t(ctx, st, NOVA_STAGE_FFN1);
-    gemm<EPI_GELU>(st, u, static_cast<const bf16_t*>(w.w_fc1), M, F, C, ep);
+    e = launch_gemm_bf16(ctx, st, EPI_GELU, u, w.w_fc1, M, F, C, ep);
   }
 
   ep.bias = static_cast<const bf16_t*>(w.b_fc2); ep.out = y; ep.ldo = C; ep.res = x1;
   {
     StageTimer t(ctx, st, NOVA_STAGE_FFN2);
-    gemm<EPI_RESIDUAL>(st, hid, static_cast<const bf16_t*>(w.w_fc2), M, C, F, ep);
+    e = launch_gemm_bf16(ctx, st, EPI_RESIDUAL, hid, w.w_fc2, M, C, F, ep);
   }
   return hipGetLastError();
 }

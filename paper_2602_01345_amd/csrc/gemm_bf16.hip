@@ -1,0 +1,318 @@
+// bf16 matrix-core GEMM of the pruned block's four projections (Sec. 3.3, "Residual Cache
+// Reuse", first equation: Layer_j on the kept rows):  out = epilogue(A W^T),
+// A [M, K] activations, W [Nout, K] weights, both K-contiguous, fp32 accumulation.
+//
+// gfx950 design:
+//  * v_mfma_f32_32x32x16_bf16; a workgroup owns a BM x BN tile, WM x WN waves own
+//    (BM/WM) x (BN/WN) sub-tiles, the K loop advances 64 elements (128 bytes per row).
+//  * Global -> LDS copies bypass the registers (global_load_lds_dwordx4): a wave instruction
+//    drops 8 rows x 128 bytes straight into LDS.  Because the LDS side of that instruction is
+//    lane-linear, the bank-conflict-avoiding XOR swizzle is applied on the global side: the
+//    lane that fills 16-byte slot p of row r fetches chunk p ^ ((r >> 1) & 7) of that row, and
+//    the MFMA operand reads look the chunk up at the same swizzled slot.
+//  * Two LDS stages: the loads of tile t+1 are in flight while tile t feeds the MFMAs; one
+//    barrier per K step.
+//  * Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs) works
+//    on a contiguous run of tiles, ordered in bands of 8 tile rows, so that the tiles in flight on
+//    one XCD form a compact rectangle and share A rows and W columns in that XCD's L2.
+#include <cstdlib>
+#include "common.h"
+#include "epilogue.h"
+#include "nova_internal.h"
+
+namespace {
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// s_waitcnt with only vmcnt = n constrained (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+#define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+
+// LDS byte offset of 16-byte chunk `c` of tile row `r`; a row holds BK elements (64 or 128 bytes).
+// The XOR term changes with every group of rows that shares a bank window, so that 16 consecutive
+// rows reading the same chunk index hit 16 different 16-byte bank groups.
+template <int BK>
+__device__ __forceinline__ int swz(int r, int c) {
+  if (BK == 64) return r * 128 + ((c ^ ((r >> 1) & 7)) << 4);
+  return r * 64 + ((c ^ ((r >> 2) & 3)) << 4);
+}
+
+template <int BM, int BN, int WM, int WN, int BK, int NST, int MODE>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __restrict__ A,
+                                                                const bf16_t* __restrict__ W, int M, int Nout,
+                                                                int K, int tiles_m, int tiles_n, int dbg,
+                                                                EpiParams<bf16_t> ep) {
+  constexpr int NW = WM * WN;
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;      // MFMA tiles per wave
+  constexpr int ROW_BYTES = BK * 2;
+  constexpr int CH = ROW_BYTES / 16;                       // 16-byte chunks per tile row
+  constexpr int RPI = 64 / CH;                             // tile rows filled by one wave load instruction
+  constexpr int LA = BM / RPI / NW, LB = BN / RPI / NW;    // load instructions per wave per stage
+  constexpr int LPW = LA + LB;
+  constexpr int KS = BK / 16;                              // MFMA K steps per stage
+  constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES, STAGE = A_BYTES + B_BYTES;
+  constexpr int CT_PITCH = BN + 8;                         // epilogue staging tile pitch (elements)
+  constexpr int CT_BYTES = BM * CT_PITCH * 2;
+  constexpr int LDS_BYTES = NST * STAGE > CT_BYTES ? NST * STAGE : CT_BYTES;
+  static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile rows must split over the waves");
+  static_assert((NST - 2) * LPW < 64, "vmcnt is a 6-bit counter");
+  __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS fill addresses stay scalar
+  const int wm = wave / WN, wn = wave % WN;
+
+  // ---- workgroup id -> tile, XCD-contiguous, M fastest -------------------------------
+  const int nblk = tiles_m * tiles_n;
+  const int L = blockIdx.x;
+  const int xcd = L & 7, j = L >> 3;
+  const int base = nblk >> 3, rem = nblk & 7;
+  const int id = xcd * base + min(xcd, rem) + j;
+  // bands of GM tile rows, column by column inside a band: the workgroups an XCD runs at the same
+  // time then cover a compact GM x (slots / GM) rectangle and share A and W tiles in its L2
+  constexpr int GM = 8;
+  const int band = id / (GM * tiles_n), in_band = id - band * (GM * tiles_n);
+  const int first_m = band * GM, rows = min(tiles_m - first_m, GM);
+  const int tn = in_band / rows, tm = first_m + (in_band - tn * rows);
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  // ---- global -> LDS: instruction i of this wave fills tile rows (i * NW + wave) * RPI + lane / CH
+  const int lr = lane / CH, lp = lane % CH;
+  const bf16_t* ga[LA];
+  const bf16_t* gb[LB];
+#pragma unroll
+  for (int i = 0; i < LA; ++i) {
+    const int r = (i * NW + wave) * RPI + lr;
+    const int c = (swz<BK>(r, lp) - r * ROW_BYTES) >> 4;   // chunk of the row that lands in slot lp
+    ga[i] = A + (int64_t)min(((dbg & 2) ? 0 : m0) + r, M - 1) * K + c * 8;   // rows past the edge re-read the last row
+  }
+#pragma unroll
+  for (int i = 0; i < LB; ++i) {
+    const int r = (i * NW + wave) * RPI + lr;
+    const int c = (swz<BK>(r, lp) - r * ROW_BYTES) >> 4;
+    gb[i] = W + (int64_t)min(((dbg & 2) ? 0 : n0) + r, Nout - 1) * K + c * 8;
+  }
+  // load instructions lo..hi-1 (A first, then W) of the tile at K offset k0 into `stage`
+  auto issue = [&](int stage, int k0, int lo, int hi) {
+    char* sa = lds + stage * STAGE;
+    char* sb = sa + A_BYTES;
+#pragma unroll
+    for (int i = 0; i < LA; ++i)
+      if (i >= lo && i < hi)
+        __builtin_amdgcn_global_load_lds((gptr_t)(ga[i] + k0), (lptr_t)(sa + (i * NW + wave) * RPI * ROW_BYTES), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < LB; ++i)
+      if (LA + i >= lo && LA + i < hi)
+        __builtin_amdgcn_global_load_lds((gptr_t)(gb[i] + k0), (lptr_t)(sb + (i * NW + wave) * RPI * ROW_BYTES), 16, 0, 0);
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][jn][r] = 0.f;
+
+  const int KT = K / BK;
+  // prologue: NST-1 tiles in flight, wait for the first
+#pragma unroll
+  for (int t = 0; t < NST - 1; ++t)
+    if (t < KT) issue(t, t * BK, 0, LPW);
+  if (KT >= NST - 1) { WAIT_VMCNT((NST - 2) * LPW); } else { WAIT_VMCNT(0); }
+  __syncthreads();
+
+  const int half = lane >> 5, r32 = lane & 31;
+  const int arow0 = wm * (BM / WM) + r32;   // tile row of this lane's A operand in MFMA tile 0
+  const int brow0 = wn * (BN / WN) + r32;
+  // swizzled byte offsets of this lane's operand chunk for the 16-wide K steps of a stage
+  int aoff[KS], boff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    aoff[ks] = swz<BK>(arow0, ks * 2 + half);
+    boff[ks] = swz<BK>(brow0, ks * 2 + half);
+  }
+  // Operand fragments are double buffered in registers and the schedule is pinned with
+  // sched_barrier: the LDS reads of K step ks+1 are issued right after the first MFMA of K step
+  // ks, so the remaining MFMAs of that step cover their latency.  The reads of the next stage's first K step are issued right
+  // after the barrier, under the MFMAs of this stage's last K step.
+  bf16x8 a[2][TM], b[2][TN];
+  auto read_frags = [&](int buf, int stage, int ks) {
+    const char* sa = lds + stage * STAGE;
+    const char* sb = sa + A_BYTES;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) a[buf][i] = *reinterpret_cast<const bf16x8*>(sa + aoff[ks] + i * 32 * ROW_BYTES);
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) b[buf][jn] = *reinterpret_cast<const bf16x8*>(sb + boff[ks] + jn * 32 * ROW_BYTES);
+  };
+  // MFMAs lo..hi-1 (flattened over the wave's TM x TN tiles) of one K step
+  auto mfmas = [&](int buf, int lo, int hi) {
+#pragma unroll
+    for (int t = 0; t < TM * TN; ++t)
+      if (t >= lo && t < hi) acc[t / TN][t % TN] = mfma32(a[buf][t / TN], b[buf][t % TN], acc[t / TN][t % TN]);
+  };
+  constexpr int LEAD = 1;                   // MFMAs issued before the next K step's LDS reads
+  static_assert(KS % 2 == 0, "fragment buffers alternate per K step");
+
+  int stage = 0, fill = NST - 1;            // stage being computed / stage being refilled
+  read_frags(0, 0, 0);
+  for (int kt = 0; kt < KT; ++kt) {
+    // the stage refilled now was read during the previous iteration and freed by its barrier
+    const bool more = kt + NST - 1 < KT;
+    const bool fillnow = more && !(dbg & 1);
+    constexpr int LPS = (LPW + KS - 2) / (KS - 1);   // fill instructions issued per K step (all but the last step)
+#pragma unroll
+    for (int ks = 0; ks < KS - 1; ++ks) {
+      mfmas(ks & 1, 0, LEAD);
+      __builtin_amdgcn_sched_barrier(0);
+      if (fillnow) issue(fill, (kt + NST - 1) * BK, ks * LPS, ks + 2 == KS ? LPW : (ks + 1) * LPS);
+      if (!(dbg & 4)) read_frags((ks + 1) & 1, stage, ks + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfmas(ks & 1, LEAD, TM * TN);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // tile kt+1 must have landed (younger tiles may stay in flight) and this wave's reads of
+    // the current stage must be complete before anyone may refill it
+    if (more) { WAIT_VMCNT((NST - 2) * LPW); } else { WAIT_VMCNT(0); }
+    __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0)
+    if (!(dbg & 8)) __syncthreads();
+    const int next = stage + 1 == NST ? 0 : stage + 1;
+    mfmas((KS - 1) & 1, 0, LEAD);
+    __builtin_amdgcn_sched_barrier(0);
+    if (kt + 1 < KT && !(dbg & 4)) read_frags(0, next, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas((KS - 1) & 1, LEAD, TM * TN);
+    __builtin_amdgcn_sched_barrier(0);
+    stage = next;
+    fill = fill + 1 == NST ? 0 : fill + 1;
+  }
+  // ---- epilogue, stage 1: accumulators (+ bias, GELU) -> bf16 tile in LDS, row-major --------
+  // lane owns column l % 32 of each MFMA tile and rows 8*(r/4) + 4*(l/32) + r%4
+  bf16_t* ct = reinterpret_cast<bf16_t*>(lds);
+#pragma unroll
+  for (int jn = 0; jn < TN; ++jn) {
+    const int lc = wn * (BN / WN) + jn * 32 + r32;
+    const int col = n0 + lc;
+    const float bias = (ep.bias && col < Nout) ? (float)ep.bias[col] : 0.0f;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int lrw = wm * (BM / WM) + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        float v = acc[i][jn][r] + bias;
+        if (MODE == EPI_GELU) v = gelu_erf(v);
+        ct[lrw * CT_PITCH + lc] = (bf16_t)v;
+      }
+  }
+  __syncthreads();
+
+  // ---- stage 2: 16-byte row chunks out of LDS, coalesced global stores ----------------------
+  constexpr int CPR = BN / 8;                       // chunks per tile row
+  for (int c = tid; c < BM * CPR; c += NW * 64) {
+    const int lrw = c / CPR, cc = c - lrw * CPR;
+    const int row = m0 + lrw, col = n0 + cc * 8;
+    if (row >= M || col >= Nout) continue;
+    bf16x8 v = *reinterpret_cast<const bf16x8*>(ct + lrw * CT_PITCH + cc * 8);
+    if (MODE == EPI_QKV) {
+      const int sel = col / ep.C, cf = col - sel * ep.C;
+      if (sel == 0) {
+        *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + cf) = v;
+      } else if (sel == 1) {
+        const int bb = row / ep.k, s = row - bb * ep.k;
+        const int head = cf / ep.dh, d = cf - head * ep.dh;
+        *reinterpret_cast<bf16x8*>(ep.kc + (((int64_t)bb * ep.heads + head) * ep.cap + ep.P + s) * ep.dh + d) = v;
+      }
+    } else if (MODE == EPI_GELU) {
+      *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + col) = v;
+    } else {
+      int64_t rrow = row;
+      int64_t rpitch = ep.ldo;
+      if (MODE == EPI_ATTN_OUT) {
+        const int bb = row / ep.k;
+        rrow = (int64_t)bb * ep.Ntok + min(max(ep.idx[row], 0), ep.Ntok - 1);
+        rpitch = ep.C;
+      }
+      const bf16x8 rs = *reinterpret_cast<const bf16x8*>(ep.res + rrow * rpitch + col);
+      bf16x8 o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = (bf16_t)((float)v[e] + (float)rs[e]);
+      *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + col) = o;
+    }
+  }
+  if (MODE == EPI_QKV) {
+    // value columns: the cache is key-minor, so walk the tile column by column with the lanes
+    // along the rows (consecutive tokens -> consecutive addresses)
+    const int v_lo = max(2 * ep.C - n0, 0);          // first tile column that is a value feature
+    const int ncol = min(BN, Nout - n0) - v_lo;
+    if (ncol > 0) {
+      for (int e = tid; e < BM * ncol; e += NW * 64) {
+        const int lc = v_lo + e / BM, lrw = e % BM;
+        const int row = m0 + lrw;
+        if (row >= M) continue;
+        const int cf = n0 + lc - 2 * ep.C;
+        const int bb = row / ep.k, s = row - bb * ep.k;
+        const int head = cf / ep.dh, d = cf - head * ep.dh;
+        ep.vc[(((int64_t)bb * ep.heads + head) * ep.dh + d) * ep.cap + ep.P + s] = ct[lrw * CT_PITCH + lc];
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WM, int WN, int BK, int NST, int MODE>
+hipError_t launch_cfg(hipStream_t st, const bf16_t* A, const bf16_t* W, int M, int Nout, int K,
+                      const EpiParams<bf16_t>& ep) {
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (Nout + BN - 1) / BN;
+  static const int dbg = getenv("NOVA_DBG") ? atoi(getenv("NOVA_DBG")) : 0;
+  gemm_bf16_kernel<BM, BN, WM, WN, BK, NST, MODE><<<tiles_m * tiles_n, WM * WN * 64, 0, st>>>(
+      A, W, M, Nout, K, tiles_m, tiles_n, dbg, ep);
+  return hipGetLastError();
+}
+
+// Tile configurations.  Larger tiles read LDS less per MFMA; smaller tiles fill the chip better
+// when M * Nout is small; more stages hide more memory latency.
+struct TileCfg { int bm, bn, per_cu; float speed; };
+constexpr int kNumCfgs = 6;
+constexpr TileCfg kCfgs[kNumCfgs] = {
+    {256, 256, 1, 1.00f},   // 0: 8 waves 128x64, BK 64, 2 stages
+    {256, 256, 1, 1.00f},   // 1: 8 waves 128x64, BK 32, 4 stages
+    {128, 128, 2, 0.90f},   // 2: 4 waves 64x64, BK 64, 2 stages, two workgroups per CU
+    {128, 128, 2, 0.90f},   // 3: 4 waves 64x64, BK 32, 4 stages, two workgroups per CU
+    {128, 128, 1, 0.60f},   // 4: 4 waves 64x64, BK 64, 4 stages
+    {256, 128, 1, 0.80f},   // 5: 8 waves 64x64, BK 64, 3 stages
+};
+
+int pick_cfg(const nova_ctx* ctx, int M, int Nout) {
+  if (ctx && ctx->gemm_cfg >= 0 && ctx->gemm_cfg < kNumCfgs) return ctx->gemm_cfg;
+  return 2;
+}
+
+template <int MODE>
+hipError_t launch_mode(const nova_ctx* ctx, hipStream_t st, const bf16_t* A, const bf16_t* W, int M, int Nout,
+                       int K, const EpiParams<bf16_t>& ep) {
+  switch (pick_cfg(ctx, M, Nout)) {
+    case 0: return launch_cfg<256, 256, 2, 4, 64, 2, MODE>(st, A, W, M, Nout, K, ep);
+    case 1: return launch_cfg<256, 256, 2, 4, 32, 4, MODE>(st, A, W, M, Nout, K, ep);
+    case 2: return launch_cfg<128, 128, 2, 2, 64, 2, MODE>(st, A, W, M, Nout, K, ep);
+    case 3: return launch_cfg<128, 128, 2, 2, 32, 4, MODE>(st, A, W, M, Nout, K, ep);
+    case 4: return launch_cfg<128, 128, 2, 2, 64, 4, MODE>(st, A, W, M, Nout, K, ep);
+    default: return launch_cfg<256, 128, 4, 2, 64, 3, MODE>(st, A, W, M, Nout, K, ep);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_gemm_bf16(const nova_ctx* ctx, hipStream_t st, int mode, const void* A, const void* W, int M,
+                            int Nout, int K, const EpiParams<bf16_t>& ep) {
+  const bf16_t* a = static_cast<const bf16_t*>(A);
+  const bf16_t* w = static_cast<const bf16_t*>(W);
+  switch (mode) {
+    case EPI_QKV: return launch_mode<EPI_QKV>(ctx, st, a, w, M, Nout, K, ep);
+    case EPI_ATTN_OUT: return launch_mode<EPI_ATTN_OUT>(ctx, st, a, w, M, Nout, K, ep);
+    case EPI_GELU: return launch_mode<EPI_GELU>(ctx, st, a, w, M, Nout, K, ep);
+    default: return launch_mode<EPI_RESIDUAL>(ctx, st, a, w, M, Nout, K, ep);
+  }
+}

@@ -21,6 +21,8 @@ struct nova_ctx {
   size_t lds_per_block;
   uint32_t prof_mask;
   std::vector<ProfRecord> prof;
+  int gemm_cfg;   // >= 0 forces one GEMM tile configuration (environment NOVA_GEMM_CFG, for tuning)
+  int attn_cfg;   // likewise for the attention kernel (NOVA_ATTN_CFG)
 };
 
 // Brackets one kernel launch with a pair of events when its stage is being timed.
@@ -74,6 +76,10 @@ hipError_t launch_gather_ln(hipStream_t st, int dtype, const void* src, const in
 hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shape& s, const nova_block_weights& w,
                             const float* x, const int32_t* idx, float* kc, float* vc, float* y,
                             const BlockWorkspace& ws);
+// gemm_bf16.hip: out = epilogue(A W^T) on the matrix cores; mode is an EpiMode
+template <typename T> struct EpiParams;
+hipError_t launch_gemm_bf16(const nova_ctx* ctx, hipStream_t st, int mode, const void* A, const void* W, int M,
+                            int Nout, int K, const EpiParams<__bf16>& ep);
 // block_bf16.hip: MFMA path
 hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_shape& s,
                              const nova_block_weights& w, const void* x, const int32_t* idx, void* kc,
