@@ -1,0 +1,302 @@
+// Flash-style attention of the kept queries over the prior-scale KV cache plus the kept
+// current keys (Sec. 3.3, "Residual Cache Reuse", first equation on the kept rows; Sec. 3.2:
+// attention is the cost that pruning saves).  bf16 operands, fp32 softmax and accumulation.
+//
+// Everything is computed transposed so that one lane owns one query column:
+//   S^T = K Q^T    A operand = key rows from LDS, B operand = query fragments held in registers
+//   O^T += V^T P^T A operand = value-cache columns from LDS (the value cache is stored key-minor
+//                  for exactly this read), B operand = the probabilities just computed, already
+//                  sitting in the lane layout the MFMA wants
+// so the online-softmax state (running max and sum) is one scalar per lane and query group, and
+// no data is exchanged between lanes except one max/sum swap between the two half-waves.
+//
+// A workgroup is 4 waves; a wave owns NQ groups of 32 queries (every K / V fragment read from LDS
+// feeds NQ MFMAs).  K and V tiles of 64 keys stream through an NST-stage LDS ring filled by
+// direct global->LDS loads; the bank-conflict XOR swizzle is applied on the global side of those
+// loads.  Workgroup ids are remapped so that all query blocks of one (batch row, head) run on the
+// same XCD at about the same time and share that head's K/V in its L2.
+#include <type_traits>
+
+#include "common.h"
+#include "nova_internal.h"
+
+namespace {
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+#define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+constexpr int ATT_WAVES = 4;
+constexpr int BKV = 64;              // keys per tile
+
+// MFMA row i of a 32-key block reads key pi(i), chosen so that the 8 scores a lane ends up holding
+// in registers 0..7 (and 8..15) belong to 8 consecutive keys: exactly the 8-key run the P^T operand
+// of the second MFMA needs from that lane.
+__device__ __forceinline__ int key_of_mfma_row(int i) {
+  const int base = i & 16, t = i & 15;
+  return base + 8 * ((t >> 2) & 1) + 4 * (t >> 3) + (t & 3);
+}
+
+// byte offset of 16-byte chunk c of row r in a swizzled tile whose rows are ROWB bytes
+template <int ROWB>
+__device__ __forceinline__ int swz(int r, int c) {
+  if (ROWB == 256) return r * 256 + ((c ^ (r & 15)) << 4);
+  return r * 128 + ((c ^ ((r >> 1) & 7)) << 4);
+}
+
+template <int DH, int NQ, int NST, int OCC>
+__global__ __launch_bounds__(ATT_WAVES * 64, OCC) void attention_bf16_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc, int k, int C,
+    int heads, int cap, int kv_total, int nqb, float scale_log2, bf16_t* __restrict__ out) {
+  constexpr int KROWB = DH * 2;                  // bytes per key row of the K tile
+  constexpr int KCH = KROWB / 16;                // chunks per key row
+  constexpr int K_BYTES = BKV * KROWB;
+  constexpr int V_BYTES = DH * 128;              // DH rows of 64 keys
+  constexpr int STAGE = K_BYTES + V_BYTES;
+  constexpr int KSTEPS = DH / 16;                // MFMAs along dh for S^T
+  constexpr int DB = DH / 32;                    // 32-row blocks of O^T
+  constexpr int K_RPI = 1024 / KROWB;            // K rows filled per wave load instruction
+  constexpr int LK = BKV / K_RPI / ATT_WAVES;    // K load instructions per wave per tile
+  constexpr int LV = DH / 8 / ATT_WAVES;         // V load instructions per wave per tile (8 rows each)
+  constexpr int LPW = LK + LV;
+  constexpr int BQ = ATT_WAVES * NQ * 32;        // queries per workgroup
+  static_assert((NST - 2) * LPW < 64, "vmcnt is a 6-bit counter");
+  __shared__ __attribute__((aligned(1024))) char lds[NST * STAGE];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int half = lane >> 5, col = lane & 31;
+
+  // ---- workgroup id -> (batch row * heads + head, query block), XCD-contiguous ------------
+  const int nblk = gridDim.x;
+  const int L = blockIdx.x;
+  const int xcd = L & 7, j = L >> 3;
+  const int id = xcd * (nblk >> 3) + min(xcd, nblk & 7) + j;
+  const int bh = id / nqb, qb = id - bh * nqb;
+  const int b = bh / heads, head = bh - b * heads;
+  const bf16_t* Kg = kc + (int64_t)bh * cap * DH;          // [cap][DH]
+  const bf16_t* Vg = vc + (int64_t)bh * DH * (int64_t)cap; // [DH][cap]
+
+  // ---- query fragments (B operand): lane = query column, 8 dh elements per K step ----------
+  bf16x8 qf[NQ][KSTEPS];
+  int qi[NQ];
+#pragma unroll
+  for (int g = 0; g < NQ; ++g) {
+    qi[g] = qb * BQ + (wave * NQ + g) * 32 + col;
+    const int qrow = min(qi[g], k - 1);                    // clamped past the edge; never stored
+    const bf16_t* qp = q + ((int64_t)b * k + qrow) * C + head * DH + half * 8;
+#pragma unroll
+    for (int t = 0; t < KSTEPS; ++t) qf[g][t] = *reinterpret_cast<const bf16x8*>(qp + t * 16);
+  }
+
+  // ---- global -> LDS fills -------------------------------------------------------------------
+  const int klr = lane / KCH, klp = lane % KCH;            // K: row within the instruction, slot
+  const int vlr = lane >> 3, vlp = lane & 7;               // V: 8 rows x 8 slots per instruction
+  int koff[LK], voff[LV];                                  // element offsets from the tile origin
+#pragma unroll
+  for (int i = 0; i < LK; ++i) {
+    const int r = (i * ATT_WAVES + wave) * K_RPI + klr;
+    const int c = (swz<KROWB>(r, klp) - r * KROWB) >> 4;
+    koff[i] = r * DH + c * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < LV; ++i) {
+    const int r = (i * ATT_WAVES + wave) * 8 + vlr;
+    const int c = (swz<128>(r, vlp) - r * 128) >> 4;
+    voff[i] = r * cap + c * 8;                             // row r of the tile is dh index r
+  }
+  auto issue = [&](int stage, int key0) {
+    char* sk = lds + stage * STAGE;
+    char* sv = sk + K_BYTES;
+    const bf16_t* kt = Kg + (int64_t)key0 * DH;
+    const bf16_t* vt = Vg + key0;
+#pragma unroll
+    for (int i = 0; i < LK; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(kt + koff[i]), (lptr_t)(sk + (i * ATT_WAVES + wave) * 1024), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < LV; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(vt + voff[i]), (lptr_t)(sv + (i * ATT_WAVES + wave) * 1024), 16, 0, 0);
+  };
+  // The last tile may reach past the valid keys.  Scores of those keys are masked below; the value
+  // columns must be exactly zero (0 * garbage could be NaN), so the wave that filled a row zeroes
+  // the invalid tail of that row once its own fill has landed.
+  auto zero_value_tail = [&](int stage, int key0) {
+    char* sv = lds + stage * STAGE + K_BYTES;
+    const int first_bad = kv_total - key0;                 // 1..63 here
+#pragma unroll
+    for (int i = 0; i < LV; ++i) {
+      const int r = (i * ATT_WAVES + wave) * 8 + vlr;
+      for (int key = first_bad + vlp; key < BKV; key += 8)
+        *reinterpret_cast<bf16_t*>(sv + swz<128>(r, key >> 3) + (key & 7) * 2) = (bf16_t)0.0f;
+    }
+  };
+
+  f32x16 o[NQ][DB];
+#pragma unroll
+  for (int g = 0; g < NQ; ++g)
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[g][d][r] = 0.f;
+  float m_run[NQ], l_run[NQ];
+#pragma unroll
+  for (int g = 0; g < NQ; ++g) { m_run[g] = -INFINITY; l_run[g] = 0.f; }
+
+  const int ntiles = (kv_total + BKV - 1) / BKV;
+#pragma unroll
+  for (int t = 0; t < NST - 1; ++t)
+    if (t < ntiles) issue(t, t * BKV);
+  if (ntiles >= NST - 1) { WAIT_VMCNT((NST - 2) * LPW); } else { WAIT_VMCNT(0); }
+  if (ntiles == 1 && kv_total < BKV) zero_value_tail(0, 0);
+  __syncthreads();
+
+  // A-operand row of this lane inside a 32-key block (see key_of_mfma_row)
+  const int krow = key_of_mfma_row(col);
+  int stage = 0, fill = NST - 1;
+  // One 64-key tile.  TAIL (last tile only) masks the scores of keys past kv_total.
+  auto tile_body = [&](auto tail_tag, int t) {
+    constexpr bool TAIL = decltype(tail_tag)::value;
+    const int key0 = t * BKV;
+    const bool more = t + NST - 1 < ntiles;
+    if (more) issue(fill, (t + NST - 1) * BKV);
+    const char* sk = lds + stage * STAGE;
+    const char* sv = sk + K_BYTES;
+
+    // ---- S^T tile: 64 keys x 32 queries per group, two 32-key blocks -------------------------
+    f32x16 s[NQ][2];
+#pragma unroll
+    for (int g = 0; g < NQ; ++g)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[g][kb][r] = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(sk + swz<KROWB>(kb * 32 + krow, ks * 2 + half));
+#pragma unroll
+        for (int g = 0; g < NQ; ++g) s[g][kb] = mfma32(a, qf[g][ks], s[g][kb]);
+      }
+
+    // ---- online softmax; register r of block kb is key key0 + kb*32 + 16*(r/8) + 8*half + r%8 ---
+    bf16x8 p[NQ][4];
+#pragma unroll
+    for (int g = 0; g < NQ; ++g) {
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          if (TAIL) {
+            const int key = key0 + kb * 32 + 16 * (r >> 3) + 8 * half + (r & 7);
+            s[g][kb][r] = key < kv_total ? s[g][kb][r] : -INFINITY;
+          }
+          tmax = fmaxf(tmax, s[g][kb][r]);
+        }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, NOVA_WAVE));
+      const float m_new = fmaxf(m_run[g], tmax);        // finite: every tile holds a valid key
+      const float mb = m_new * scale_log2;
+      float psum = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float e = __builtin_amdgcn_exp2f(fmaf(s[g][kb][r], scale_log2, -mb));
+          psum += e;
+          p[g][kb * 2 + (r >> 3)][r & 7] = (bf16_t)e;
+        }
+      // rescale only when some query of the wave saw a new maximum (rare after the first tiles)
+      if (__any(m_new != m_run[g])) {
+        const float alpha = __builtin_amdgcn_exp2f((m_run[g] - m_new) * scale_log2);
+        l_run[g] *= alpha;
+#pragma unroll
+        for (int d = 0; d < DB; ++d)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[g][d][r] *= alpha;
+      }
+      l_run[g] += psum;
+      m_run[g] = m_new;
+    }
+
+    // ---- O^T += V^T P^T : DH rows x 32 queries per group, 4 runs of 16 keys --------------------
+#pragma unroll
+    for (int kg = 0; kg < 4; ++kg)
+#pragma unroll
+      for (int d = 0; d < DB; ++d) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(sv + swz<128>(d * 32 + col, kg * 2 + half));
+#pragma unroll
+        for (int g = 0; g < NQ; ++g) o[g][d] = mfma32(a, p[g][kg], o[g][d]);
+      }
+
+    // tile t+1 must have landed; this wave's LDS reads of the current stage must be complete
+    if (more) { WAIT_VMCNT((NST - 2) * LPW); } else { WAIT_VMCNT(0); }
+    if (t + 2 == ntiles && (t + 2) * BKV > kv_total) zero_value_tail(stage + 1 == NST ? 0 : stage + 1, (t + 1) * BKV);
+    __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0)
+    __syncthreads();
+    stage = stage + 1 == NST ? 0 : stage + 1;
+    fill = fill + 1 == NST ? 0 : fill + 1;
+  };
+  for (int t = 0; t + 1 < ntiles; ++t) tile_body(std::false_type{}, t);
+  tile_body(std::true_type{}, ntiles - 1);
+
+#pragma unroll
+  for (int g = 0; g < NQ; ++g) {
+    const float l_tot = l_run[g] + __shfl_xor(l_run[g], 32, NOVA_WAVE);
+    const float inv = 1.0f / l_tot;
+    if (qi[g] < k) {
+      bf16_t* op = out + ((int64_t)b * k + qi[g]) * C + head * DH;
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          bf16x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = (bf16_t)(o[g][d][r4 * 4 + e] * inv);
+          *reinterpret_cast<bf16x4*>(op + d * 32 + r4 * 8 + half * 4) = v;
+        }
+    }
+  }
+}
+
+template <int DH, int NQ, int NST, int OCC>
+hipError_t launch_cfg(hipStream_t st, const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int B, int k, int C,
+                      int heads, int cap, int kv_total, float scale_log2, bf16_t* out) {
+  constexpr int BQ = ATT_WAVES * NQ * 32;
+  const int nqb = (k + BQ - 1) / BQ;
+  attention_bf16_kernel<DH, NQ, NST, OCC><<<nqb * heads * B, ATT_WAVES * 64, 0, st>>>(q, kc, vc, k, C, heads, cap,
+                                                                                kv_total, nqb, scale_log2, out);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void* qv, const void* kcv,
+                                 const void* vcv, int B, int k, int C, int heads, int cap, int kv_total, void* outv) {
+  const bf16_t* q = static_cast<const bf16_t*>(qv);
+  const bf16_t* kc = static_cast<const bf16_t*>(kcv);
+  const bf16_t* vc = static_cast<const bf16_t*>(vcv);
+  bf16_t* out = static_cast<bf16_t*>(outv);
+  const int dh = C / heads;
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)dh);
+  // One group of 32 queries per wave (two workgroups per CU, so that one wave's softmax overlaps
+  // another wave's MFMAs); two groups per wave (half the LDS reads per MFMA, one workgroup per
+  // CU) can be forced for tuning.
+  (void)B;
+  int nq = ctx ? ctx->attn_cfg : -1;
+  if (nq < 1 || nq > 2) nq = 1;
+#define ATT_LAUNCH(DH_, NQ_, NST_, OCC_) \
+  return launch_cfg<DH_, NQ_, NST_, OCC_>(st, q, kc, vc, B, k, C, heads, cap, kv_total, scale_log2, out)
+  if (dh == 64) {
+    if (nq == 1) ATT_LAUNCH(64, 1, 2, 2);
+    ATT_LAUNCH(64, 2, 3, 1);
+  }
+  if (nq == 1) ATT_LAUNCH(128, 1, 2, 2);
+  ATT_LAUNCH(128, 2, 3, 1);
+#undef ATT_LAUNCH
+}

@@ -80,6 +80,9 @@ hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shap
 template <typename T> struct EpiParams;
 hipError_t launch_gemm_bf16(const nova_ctx* ctx, hipStream_t st, int mode, const void* A, const void* W, int M,
                             int Nout, int K, const EpiParams<__bf16>& ep);
+// attention_bf16.hip: attn[B*k, C] = softmax(q K^T / sqrt(dh)) V per head over kv_total cached keys
+hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void* q, const void* kc, const void* vc,
+                                 int B, int k, int C, int heads, int cap, int kv_total, void* out);
 // block_bf16.hip: MFMA path
 hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_shape& s,
                              const nova_block_weights& w, const void* x, const int32_t* idx, void* kc,
