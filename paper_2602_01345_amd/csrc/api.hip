@@ -51,6 +51,12 @@ BlockWorkspace carve_workspace(const nova_block_shape& s, void* base) {
   w.attn = p + off; off += up256(M * C * e);
   w.x1 = p + off;   off += up256(M * C * e);
   w.hid = p + off;  off += up256(M * F * e);
+  w.part_o = w.part_ml = nullptr;
+  if (s.dtype == NOVA_BF16) {
+    const size_t ns = (size_t)attention_max_split();
+    w.part_o = p + off;  off += up256(ns * M * C * 4);
+    w.part_ml = p + off; off += up256(ns * M * (size_t)s.heads * 2 * 4);
+  }
   w.total = off;
   return w;
 }
@@ -75,6 +81,8 @@ int nova_create(nova_ctx** out, int device_id) {
   const char* a = getenv("NOVA_ATTN_CFG");
   c->gemm_cfg = g ? atoi(g) : -1;
   c->attn_cfg = a ? atoi(a) : -1;
+  const char* sp = getenv("NOVA_ATTN_SPLIT");
+  c->attn_split = sp ? atoi(sp) : -1;
   *out = c;
   return NOVA_OK;
 }

@@ -15,6 +15,7 @@
 // direct global->LDS loads; the bank-conflict XOR swizzle is applied on the global side of those
 // loads.  Workgroup ids are remapped so that all query blocks of one (batch row, head) run on the
 // same XCD at about the same time and share that head's K/V in its L2.
+#include <algorithm>
 #include <type_traits>
 
 #include "common.h"
@@ -33,6 +34,7 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 
 constexpr int ATT_WAVES = 4;
 constexpr int BKV = 64;              // keys per tile
+constexpr int kMaxSplit = 4;         // most key splits a launch may use (sizes the partial-result workspace)
 
 // MFMA row i of a 32-key block reads key pi(i), chosen so that the 8 scores a lane ends up holding
 // in registers 0..7 (and 8..15) belong to 8 consecutive keys: exactly the 8-key run the P^T operand
@@ -52,7 +54,8 @@ __device__ __forceinline__ int swz(int r, int c) {
 template <int DH, int NQ, int NST, int OCC>
 __global__ __launch_bounds__(ATT_WAVES * 64, OCC) void attention_bf16_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc, int k, int C,
-    int heads, int cap, int kv_total, int nqb, float scale_log2, bf16_t* __restrict__ out) {
+    int heads, int cap, int kv_total, int nqb, int nsplit, int64_t part_rows, float scale_log2,
+    bf16_t* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml) {
   constexpr int KROWB = DH * 2;                  // bytes per key row of the K tile
   constexpr int KCH = KROWB / 16;                // chunks per key row
   constexpr int K_BYTES = BKV * KROWB;
@@ -77,7 +80,10 @@ __global__ __launch_bounds__(ATT_WAVES * 64, OCC) void attention_bf16_kernel(
   const int L = blockIdx.x;
   const int xcd = L & 7, j = L >> 3;
   const int id = xcd * (nblk >> 3) + min(xcd, nblk & 7) + j;
-  const int bh = id / nqb, qb = id - bh * nqb;
+  // id -> (batch row * heads + head, query block, key split); the splits of one query block are neighbours
+  const int per_bh = nqb * nsplit;
+  const int bh = id / per_bh, rest = id - bh * per_bh;
+  const int qb = rest / nsplit, split = rest - qb * nsplit;
   const int b = bh / heads, head = bh - b * heads;
   const bf16_t* Kg = kc + (int64_t)bh * cap * DH;          // [cap][DH]
   const bf16_t* Vg = vc + (int64_t)bh * DH * (int64_t)cap; // [DH][cap]
@@ -147,12 +153,16 @@ __global__ __launch_bounds__(ATT_WAVES * 64, OCC) void attention_bf16_kernel(
 #pragma unroll
   for (int g = 0; g < NQ; ++g) { m_run[g] = -INFINITY; l_run[g] = 0.f; }
 
-  const int ntiles = (kv_total + BKV - 1) / BKV;
+  // this workgroup's run of key tiles [t_begin, t_end)
+  const int ntiles_all = (kv_total + BKV - 1) / BKV;
+  const int tps = (ntiles_all + nsplit - 1) / nsplit;
+  const int t_begin = split * tps;
+  const int ntiles = min(ntiles_all, t_begin + tps);       // exclusive end; >= t_begin + 1 (host guarantees)
 #pragma unroll
   for (int t = 0; t < NST - 1; ++t)
-    if (t < ntiles) issue(t, t * BKV);
-  if (ntiles >= NST - 1) { WAIT_VMCNT((NST - 2) * LPW); } else { WAIT_VMCNT(0); }
-  if (ntiles == 1 && kv_total < BKV) zero_value_tail(0, 0);
+    if (t_begin + t < ntiles) issue(t, (t_begin + t) * BKV);
+  if (ntiles - t_begin >= NST - 1) { WAIT_VMCNT((NST - 2) * LPW); } else { WAIT_VMCNT(0); }
+  if (t_begin + 1 == ntiles_all && kv_total < ntiles_all * BKV) zero_value_tail(0, t_begin * BKV);
   __syncthreads();
 
   // A-operand row of this lane inside a 32-key block (see key_of_mfma_row)
@@ -168,6 +178,12 @@ __global__ __launch_bounds__(ATT_WAVES * 64, OCC) void attention_bf16_kernel(
     const char* sv = sk + K_BYTES;
 
     // ---- S^T tile: 64 keys x 32 queries per group, two 32-key blocks -------------------------
+    // Key fragments travel through a two-deep register ring of GF fragments.  The schedule is
+    // pinned: first MFMA of a group, then the LDS reads of the next group, then the group's other
+    // MFMAs -- so the wait in front of the next group finds its fragments (almost) landed.
+    constexpr int NF = 2 * KSTEPS;            // fragments per tile; fragment f = (kb = f / KSTEPS, ks = f % KSTEPS)
+    constexpr int GF = 4;                     // fragments per group
+    static_assert(NF % GF == 0, "groups tile the fragments");
     f32x16 s[NQ][2];
 #pragma unroll
     for (int g = 0; g < NQ; ++g)
@@ -175,14 +191,34 @@ __global__ __launch_bounds__(ATT_WAVES * 64, OCC) void attention_bf16_kernel(
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[g][kb][r] = 0.f;
+    bf16x8 kf[2][GF];
+    auto read_k = [&](int buf, int f0) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int ks = 0; ks < KSTEPS; ++ks) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(sk + swz<KROWB>(kb * 32 + krow, ks * 2 + half));
-#pragma unroll
-        for (int g = 0; g < NQ; ++g) s[g][kb] = mfma32(a, qf[g][ks], s[g][kb]);
+      for (int i = 0; i < GF; ++i) {
+        const int f = f0 + i;
+        kf[buf][i] = *reinterpret_cast<const bf16x8*>(sk + swz<KROWB>((f / KSTEPS) * 32 + krow, (f % KSTEPS) * 2 + half));
       }
+    };
+    auto mfma_k = [&](int buf, int f0, int lo, int hi) {
+#pragma unroll
+      for (int i = 0; i < GF; ++i)
+        if (i >= lo && i < hi) {
+          const int f = f0 + i;
+#pragma unroll
+          for (int g = 0; g < NQ; ++g) s[g][f / KSTEPS] = mfma32(kf[buf][i], qf[g][f % KSTEPS], s[g][f / KSTEPS]);
+        }
+    };
+    read_k(0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int grp = 0; grp < NF / GF; ++grp) {
+      mfma_k(grp & 1, grp * GF, 0, 1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (grp + 1 < NF / GF) read_k((grp + 1) & 1, (grp + 1) * GF);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_k(grp & 1, grp * GF, 1, GF);
+      __builtin_amdgcn_sched_barrier(0);
+    }
 
     // ---- online softmax; register r of block kb is key key0 + kb*32 + 16*(r/8) + 8*half + r%8 ---
     bf16x8 p[NQ][4];
@@ -236,21 +272,23 @@ __global__ __launch_bounds__(ATT_WAVES * 64, OCC) void attention_bf16_kernel(
 
     // tile t+1 must have landed; this wave's LDS reads of the current stage must be complete
     if (more) { WAIT_VMCNT((NST - 2) * LPW); } else { WAIT_VMCNT(0); }
-    if (t + 2 == ntiles && (t + 2) * BKV > kv_total) zero_value_tail(stage + 1 == NST ? 0 : stage + 1, (t + 1) * BKV);
+    if (t + 2 == ntiles_all && (t + 2) * BKV > kv_total) zero_value_tail(stage + 1 == NST ? 0 : stage + 1, (t + 1) * BKV);
     __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0)
     __syncthreads();
     stage = stage + 1 == NST ? 0 : stage + 1;
     fill = fill + 1 == NST ? 0 : fill + 1;
   };
-  for (int t = 0; t + 1 < ntiles; ++t) tile_body(std::false_type{}, t);
+  for (int t = t_begin; t + 1 < ntiles; ++t) tile_body(std::false_type{}, t);
   tile_body(std::true_type{}, ntiles - 1);
 
 #pragma unroll
   for (int g = 0; g < NQ; ++g) {
     const float l_tot = l_run[g] + __shfl_xor(l_run[g], 32, NOVA_WAVE);
-    const float inv = 1.0f / l_tot;
-    if (qi[g] < k) {
-      bf16_t* op = out + ((int64_t)b * k + qi[g]) * C + head * DH;
+    if (qi[g] >= k) continue;
+    const int64_t row = (int64_t)b * k + qi[g];
+    if (nsplit == 1) {
+      const float inv = 1.0f / l_tot;
+      bf16_t* op = out + row * C + head * DH;
 #pragma unroll
       for (int d = 0; d < DB; ++d)
 #pragma unroll
@@ -260,24 +298,99 @@ __global__ __launch_bounds__(ATT_WAVES * 64, OCC) void attention_bf16_kernel(
           for (int e = 0; e < 4; ++e) v[e] = (bf16_t)(o[g][d][r4 * 4 + e] * inv);
           *reinterpret_cast<bf16x4*>(op + d * 32 + r4 * 8 + half * 4) = v;
         }
+    } else {
+      // unnormalised partial sums of this key split, merged by attention_combine_kernel
+      float* po = part_o + ((int64_t)split * part_rows + row) * C + head * DH;
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          f32x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = o[g][d][r4 * 4 + e];
+          *reinterpret_cast<f32x4*>(po + d * 32 + r4 * 8 + half * 4) = v;
+        }
+      if (half == 0) {
+        float* pm = part_ml + (((int64_t)split * part_rows + row) * heads + head) * 2;
+        pm[0] = m_run[g];
+        pm[1] = l_tot;
+      }
     }
   }
 }
 
+// Merge of the key splits: out = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^((m_s - max_s m_s) c).
+template <int DH>
+__global__ __launch_bounds__(256) void attention_combine_kernel(const float* __restrict__ part_o,
+                                                                const float* __restrict__ part_ml, int64_t rows,
+                                                                int C, int heads, int nsplit, float scale_log2,
+                                                                bf16_t* __restrict__ out) {
+  const int64_t nvec = rows * (C / 4);
+  for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t row = v / (C / 4);
+    const int c = (int)(v - row * (C / 4)) * 4;
+    const int head = c / DH;
+    float mmax = -INFINITY;
+    for (int s = 0; s < nsplit; ++s) mmax = fmaxf(mmax, part_ml[((s * rows + row) * heads + head) * 2]);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float l = 0.f;
+    for (int s = 0; s < nsplit; ++s) {
+      const float* pm = part_ml + ((s * rows + row) * heads + head) * 2;
+      const float w = __builtin_amdgcn_exp2f((pm[0] - mmax) * scale_log2);
+      l = fmaf(w, pm[1], l);
+      const f32x4 o = *reinterpret_cast<const f32x4*>(part_o + (s * rows + row) * C + c);
+      acc += w * o;
+    }
+    const float inv = 1.0f / l;
+    bf16x4 r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r[e] = (bf16_t)(acc[e] * inv);
+    *reinterpret_cast<bf16x4*>(out + row * C + c) = r;
+  }
+}
+
 template <int DH, int NQ, int NST, int OCC>
-hipError_t launch_cfg(hipStream_t st, const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int B, int k, int C,
-                      int heads, int cap, int kv_total, float scale_log2, bf16_t* out) {
+hipError_t launch_cfg(const nova_ctx* ctx, hipStream_t st, const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int B,
+                      int k, int C, int heads, int cap, int kv_total, float scale_log2, bf16_t* out, float* part_o,
+                      float* part_ml) {
   constexpr int BQ = ATT_WAVES * NQ * 32;
   const int nqb = (k + BQ - 1) / BQ;
-  attention_bf16_kernel<DH, NQ, NST, OCC><<<nqb * heads * B, ATT_WAVES * 64, 0, st>>>(q, kc, vc, k, C, heads, cap,
-                                                                                kv_total, nqb, scale_log2, out);
+  const int blocks = nqb * heads * B;
+  // Key splits: with few, equally long workgroups the last round over the CUs can be mostly
+  // empty; splitting the key range makes the rounds finer at the price of one small merge pass.
+  const int slots = (ctx ? ctx->num_cus : 256) * OCC;
+  const int ntiles = (kv_total + BKV - 1) / BKV;
+  int nsplit = 1;
+  if (part_o && part_ml) {
+    float best = 1e30f;
+    // a split count is usable when every split still owns at least one tile
+    auto usable = [&](int s) { return s >= 1 && s <= kMaxSplit && (s - 1) * ((ntiles + s - 1) / s) < ntiles; };
+    for (int s = 1; s <= kMaxSplit; ++s) {
+      if (s > 1 && (ntiles / s < 8 || !usable(s))) break;
+      const float rounds = (float)((blocks * s + slots - 1) / slots);
+      const float cost = rounds / s * (s > 1 ? 1.06f : 1.0f);
+      if (cost < best - 1e-6f) { best = cost; nsplit = s; }
+    }
+    if (ctx && usable(ctx->attn_split)) nsplit = ctx->attn_split;
+  }
+  const int64_t rows = (int64_t)B * k;
+  attention_bf16_kernel<DH, NQ, NST, OCC><<<blocks * nsplit, ATT_WAVES * 64, 0, st>>>(
+      q, kc, vc, k, C, heads, cap, kv_total, nqb, nsplit, rows, scale_log2, out, part_o, part_ml);
+  if (nsplit > 1) {
+    const int64_t nvec = rows * (C / 4);
+    const unsigned grid = (unsigned)std::min<int64_t>((nvec + 255) / 256, 65535);
+    attention_combine_kernel<DH><<<grid, 256, 0, st>>>(part_o, part_ml, rows, C, heads, nsplit, scale_log2, out);
+  }
   return hipGetLastError();
 }
 
 }  // namespace
 
+int attention_max_split() { return kMaxSplit; }
+
 hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void* qv, const void* kcv,
-                                 const void* vcv, int B, int k, int C, int heads, int cap, int kv_total, void* outv) {
+                                 const void* vcv, int B, int k, int C, int heads, int cap, int kv_total, void* outv,
+                                 float* part_o, float* part_ml) {
   const bf16_t* q = static_cast<const bf16_t*>(qv);
   const bf16_t* kc = static_cast<const bf16_t*>(kcv);
   const bf16_t* vc = static_cast<const bf16_t*>(vcv);
@@ -287,13 +400,13 @@ hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void
   // One group of 32 queries per wave (two workgroups per CU, so that one wave's softmax overlaps
   // another wave's MFMAs); two groups per wave (half the LDS reads per MFMA, one workgroup per
   // CU) can be forced for tuning.
-  (void)B;
   int nq = ctx ? ctx->attn_cfg : -1;
   if (nq < 1 || nq > 2) nq = 1;
-#define ATT_LAUNCH(DH_, NQ_, NST_, OCC_) \
-  return launch_cfg<DH_, NQ_, NST_, OCC_>(st, q, kc, vc, B, k, C, heads, cap, kv_total, scale_log2, out)
+#define ATT_LAUNCH(DH_, NQ_, NST_, OCC_)                                                                       \
+  return launch_cfg<DH_, NQ_, NST_, OCC_>(ctx, st, q, kc, vc, B, k, C, heads, cap, kv_total, scale_log2, out, \
+                                          part_o, part_ml)
   if (dh == 64) {
-    if (nq == 1) ATT_LAUNCH(64, 1, 2, 2);
+    if (nq == 1) ATT_LAUNCH(64, 1, 2, 3);
     ATT_LAUNCH(64, 2, 3, 1);
   }
   if (nq == 1) ATT_LAUNCH(128, 1, 2, 2);

@@ -43,7 +43,8 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
 
   {
     StageTimer t(ctx, st, NOVA_STAGE_ATTENTION);
-    e = launch_attention_bf16(ctx, st, q, kc, vc, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len + s.k, attn);
+    e = launch_attention_bf16(ctx, st, q, kc, vc, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len + s.k, attn,
+                              reinterpret_cast<float*>(ws.part_o), reinterpret_cast<float*>(ws.part_ml));
   }
   if (e != hipSuccess) return e;
 

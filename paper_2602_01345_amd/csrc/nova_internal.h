@@ -23,6 +23,7 @@ struct nova_ctx {
   std::vector<ProfRecord> prof;
   int gemm_cfg;   // >= 0 forces one GEMM tile configuration (environment NOVA_GEMM_CFG, for tuning)
   int attn_cfg;   // likewise for the attention kernel (NOVA_ATTN_CFG)
+  int attn_split; // >= 1 forces the number of attention key splits (NOVA_ATTN_SPLIT)
 };
 
 // Brackets one kernel launch with a pair of events when its stage is being timed.
@@ -64,6 +65,8 @@ struct BlockWorkspace {
   char* attn;  // [M, C]  attention output
   char* x1;    // [M, C]  residual stream after attention
   char* hid;   // [M, F]  FFN hidden
+  char* part_o;   // bf16 path: [max_split, M, C] fp32 attention partial sums
+  char* part_ml;  // bf16 path: [max_split, M, heads, 2] fp32 running max / sum
   size_t total;
 };
 BlockWorkspace carve_workspace(const nova_block_shape& s, void* base);
@@ -81,8 +84,12 @@ template <typename T> struct EpiParams;
 hipError_t launch_gemm_bf16(const nova_ctx* ctx, hipStream_t st, int mode, const void* A, const void* W, int M,
                             int Nout, int K, const EpiParams<__bf16>& ep);
 // attention_bf16.hip: attn[B*k, C] = softmax(q K^T / sqrt(dh)) V per head over kv_total cached keys
+// part_o / part_ml: workspace for split-key partial results ([max_split, B*k, C] and [max_split, B*k, heads, 2]
+// fp32), or nullptr to forbid splitting
+int attention_max_split();
 hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void* q, const void* kc, const void* vc,
-                                 int B, int k, int C, int heads, int cap, int kv_total, void* out);
+                                 int B, int k, int C, int heads, int cap, int kv_total, void* out, float* part_o,
+                                 float* part_ml);
 // block_bf16.hip: MFMA path
 hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_shape& s,
                              const nova_block_weights& w, const void* x, const int32_t* idx, void* kc,
