@@ -210,6 +210,46 @@ def main():
                 ent["frac_mfma_peak"] = rate / 1e12 / MFMA_BF16_PEAK_TFLOPS
             kernels[name] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in ent.items()}
 
+    # sustained HBM rate of the bandwidth-bound calls: the L blocks' launches back to back under one
+    # pair of events (an isolated 60 MB launch is dominated by launch ramp; a plain read kernel of
+    # that size behaves the same), every launch on its own, distinct tensors
+    hbm = {}
+    if not args.no_stage_pass:
+        def sustained(name, fn):
+            fn()                                   # warm the code path
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            total = sum(w[name][1] for w in work)
+            hbm[name] = {"us_per_launch": round(ms * 1e3 / len(work), 2), "GB/s": round(total / (ms * 1e-3) / 1e9, 1),
+                         "frac_hbm_peak": round(total / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        blocks = runner.blocks
+        sustained("entropy", lambda: [nova.entropy(st.logits, st.entropy) for st in blocks])
+        if wl.dtype == "bf16":
+            # the same kernel on fp32 logits (twice the bytes, the same arithmetic)
+            f32 = [(torch.randn((wl.B, scale.N, wl.V), generator=gen, device="cuda") * 3.0) for _ in range(8)]
+            Hs = [torch.empty((wl.B, scale.N), dtype=torch.float32, device="cuda") for _ in f32]
+            work_f32 = [{"entropy_f32": ("bytes", wl.B * scale.N * (wl.V * 4 + 4))}] * len(f32)
+            keep, work = work, work_f32
+            sustained("entropy_f32", lambda: [nova.entropy(a, h) for a, h in zip(f32, Hs)])
+            work = keep
+            del f32, Hs
+        sustained("select", lambda: [nova.select(st.entropy, st.k, st.kept_idx, st.keep_mask) for st in blocks])
+        sustained("merge", lambda: [nova.merge_cache(scale.grid, scale.grid, scale.prev_grid, scale.prev_grid, st.k, x,
+                                                     st.y_kept, st.kept_idx, st.keep_mask, st.cache_prev, st.out,
+                                                     st.cache_new) for st in blocks])
+
+    traffic = None
+    tf = os.path.join(ROOT, "profiles", f"attention_{args.config}_hbm_traffic.txt")
+    if os.path.exists(tf):
+        for line in open(tf):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = float(line.split(":")[1])
+
     out = {
         "metric": METRIC, "value": kept / (ms_step * 1e-3), "unit": "kept tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
@@ -218,11 +258,12 @@ def main():
         "config": {"workload": f"{wl.name}: last scale {scale.grid}x{scale.grid}, B={wl.B}, C={wl.C}, heads={wl.heads}, "
                                f"L={wl.L}, V={wl.V}, P={scale.kv_len}, keep {wl.keep_hi}->{wl.keep_lo}",
                    "kept_tokens_per_step": kept, "blocks": wl.L},
-        "roofline": {"kernel": f"attention_bf16_kernel<{wl.dh}>", "bound": "mfma", "achieved": achieved,
-                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": None, "launches": dom_n, "avg_launch_us": dom_avg_s * 1e6,
-                     "flops_per_launch": dom_flops},
+        "roofline": {"kernel": f"attention_bf16_kernel<{wl.dh},...> (+ its split-merge pass)", "bound": "mfma",
+                     "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic, "launches": dom_n,
+                     "avg_launch_us": dom_avg_s * 1e6, "flops_per_launch": dom_flops},
         "kernels": kernels,
+        "hbm_kernels_sustained": hbm,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(hb0, wl, scale, ks[0])

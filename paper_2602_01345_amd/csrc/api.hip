@@ -152,7 +152,7 @@ int nova_entropy(nova_ctx* ctx, void* stream, const void* logits, int logits_dty
   if ((reinterpret_cast<uintptr_t>(logits) % esize(logits_dtype)) != 0) return NOVA_ERR_INVALID_ARG;
   if (int rc = set_device(ctx)) return rc;
   StageTimer timer(ctx, static_cast<hipStream_t>(stream), NOVA_STAGE_ENTROPY);
-  hipError_t e = launch_entropy(static_cast<hipStream_t>(stream), logits, logits_dtype, rows_per_batch, batch, V,
+  hipError_t e = launch_entropy(static_cast<hipStream_t>(stream), ctx->num_cus, logits, logits_dtype, rows_per_batch, batch, V,
                                 row_stride_elems, entropy, mean_entropy);
   return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
 }

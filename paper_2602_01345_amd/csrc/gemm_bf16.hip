@@ -15,7 +15,6 @@
 //  * Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs) works
 //    on a contiguous run of tiles, ordered in bands of 8 tile rows, so that the tiles in flight on
 //    one XCD form a compact rectangle and share A rows and W columns in that XCD's L2.
-#include <cstdlib>
 #include "common.h"
 #include "epilogue.h"
 #include "nova_internal.h"
@@ -44,7 +43,7 @@ __device__ __forceinline__ int swz(int r, int c) {
 template <int BM, int BN, int WM, int WN, int BK, int NST, int MODE>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __restrict__ A,
                                                                 const bf16_t* __restrict__ W, int M, int Nout,
-                                                                int K, int tiles_m, int tiles_n, int dbg,
+                                                                int K, int tiles_m, int tiles_n,
                                                                 EpiParams<bf16_t> ep) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;      // MFMA tiles per wave
@@ -88,13 +87,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
   for (int i = 0; i < LA; ++i) {
     const int r = (i * NW + wave) * RPI + lr;
     const int c = (swz<BK>(r, lp) - r * ROW_BYTES) >> 4;   // chunk of the row that lands in slot lp
-    ga[i] = A + (int64_t)min(((dbg & 2) ? 0 : m0) + r, M - 1) * K + c * 8;   // rows past the edge re-read the last row
+    ga[i] = A + (int64_t)min(m0 + r, M - 1) * K + c * 8;   // rows past the edge re-read the last row
   }
 #pragma unroll
   for (int i = 0; i < LB; ++i) {
     const int r = (i * NW + wave) * RPI + lr;
     const int c = (swz<BK>(r, lp) - r * ROW_BYTES) >> 4;
-    gb[i] = W + (int64_t)min(((dbg & 2) ? 0 : n0) + r, Nout - 1) * K + c * 8;
+    gb[i] = W + (int64_t)min(n0 + r, Nout - 1) * K + c * 8;
   }
   // load instructions lo..hi-1 (A first, then W) of the tile at K offset k0 into `stage`
   auto issue = [&](int stage, int k0, int lo, int hi) {
@@ -138,8 +137,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
   }
   // Operand fragments are double buffered in registers and the schedule is pinned with
   // sched_barrier: the LDS reads of K step ks+1 are issued right after the first MFMA of K step
-  // ks, so the remaining MFMAs of that step cover their latency.  The reads of the next stage's first K step are issued right
-  // after the barrier, under the MFMAs of this stage's last K step.
+  // ks, so the remaining MFMAs of that step cover their latency.  The reads of the next stage's
+  // first K step are issued right after the barrier, under the MFMAs of this stage's last K step.
   bf16x8 a[2][TM], b[2][TN];
   auto read_frags = [&](int buf, int stage, int ks) {
     const char* sa = lds + stage * STAGE;
@@ -163,14 +162,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
   for (int kt = 0; kt < KT; ++kt) {
     // the stage refilled now was read during the previous iteration and freed by its barrier
     const bool more = kt + NST - 1 < KT;
-    const bool fillnow = more && !(dbg & 1);
     constexpr int LPS = (LPW + KS - 2) / (KS - 1);   // fill instructions issued per K step (all but the last step)
 #pragma unroll
     for (int ks = 0; ks < KS - 1; ++ks) {
       mfmas(ks & 1, 0, LEAD);
       __builtin_amdgcn_sched_barrier(0);
-      if (fillnow) issue(fill, (kt + NST - 1) * BK, ks * LPS, ks + 2 == KS ? LPW : (ks + 1) * LPS);
-      if (!(dbg & 4)) read_frags((ks + 1) & 1, stage, ks + 1);
+      if (more) issue(fill, (kt + NST - 1) * BK, ks * LPS, ks + 2 == KS ? LPW : (ks + 1) * LPS);
+      read_frags((ks + 1) & 1, stage, ks + 1);
       __builtin_amdgcn_sched_barrier(0);
       mfmas(ks & 1, LEAD, TM * TN);
       __builtin_amdgcn_sched_barrier(0);
@@ -179,11 +177,11 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
     // the current stage must be complete before anyone may refill it
     if (more) { WAIT_VMCNT((NST - 2) * LPW); } else { WAIT_VMCNT(0); }
     __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0)
-    if (!(dbg & 8)) __syncthreads();
+    __syncthreads();
     const int next = stage + 1 == NST ? 0 : stage + 1;
     mfmas((KS - 1) & 1, 0, LEAD);
     __builtin_amdgcn_sched_barrier(0);
-    if (kt + 1 < KT && !(dbg & 4)) read_frags(0, next, 0);
+    if (kt + 1 < KT) read_frags(0, next, 0);
     __builtin_amdgcn_sched_barrier(0);
     mfmas((KS - 1) & 1, LEAD, TM * TN);
     __builtin_amdgcn_sched_barrier(0);
@@ -266,40 +264,32 @@ template <int BM, int BN, int WM, int WN, int BK, int NST, int MODE>
 hipError_t launch_cfg(hipStream_t st, const bf16_t* A, const bf16_t* W, int M, int Nout, int K,
                       const EpiParams<bf16_t>& ep) {
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (Nout + BN - 1) / BN;
-  static const int dbg = getenv("NOVA_DBG") ? atoi(getenv("NOVA_DBG")) : 0;
   gemm_bf16_kernel<BM, BN, WM, WN, BK, NST, MODE><<<tiles_m * tiles_n, WM * WN * 64, 0, st>>>(
-      A, W, M, Nout, K, tiles_m, tiles_n, dbg, ep);
+      A, W, M, Nout, K, tiles_m, tiles_n, ep);
   return hipGetLastError();
 }
 
-// Tile configurations.  Larger tiles read LDS less per MFMA; smaller tiles fill the chip better
-// when M * Nout is small; more stages hide more memory latency.
-struct TileCfg { int bm, bn, per_cu; float speed; };
-constexpr int kNumCfgs = 6;
-constexpr TileCfg kCfgs[kNumCfgs] = {
-    {256, 256, 1, 1.00f},   // 0: 8 waves 128x64, BK 64, 2 stages
-    {256, 256, 1, 1.00f},   // 1: 8 waves 128x64, BK 32, 4 stages
-    {128, 128, 2, 0.90f},   // 2: 4 waves 64x64, BK 64, 2 stages, two workgroups per CU
-    {128, 128, 2, 0.90f},   // 3: 4 waves 64x64, BK 32, 4 stages, two workgroups per CU
-    {128, 128, 1, 0.60f},   // 4: 4 waves 64x64, BK 64, 4 stages
-    {256, 128, 1, 0.80f},   // 5: 8 waves 64x64, BK 64, 3 stages
-};
+// Tile configurations (NOVA_GEMM_CFG forces one, for tuning):
+//   0: 128x128x64, 4 waves of 64x64, 2 LDS stages, two workgroups per CU   (default)
+//   1: 256x256x64, 8 waves of 128x64, 2 LDS stages, one workgroup per CU
+//   2: 256x128x64, 8 waves of 64x64, 3 LDS stages, one workgroup per CU
+// Measured on MI355X at the workloads' shapes (M = 1.6k..4.9k, N, K = 2k..8k) the first one wins:
+// two independent workgroups per CU overlap one tile's prologue / epilogue with the other's MFMAs
+// and quantise better over the 256 CUs.
+constexpr int kNumCfgs = 3;
 
-int pick_cfg(const nova_ctx* ctx, int M, int Nout) {
+int pick_cfg(const nova_ctx* ctx) {
   if (ctx && ctx->gemm_cfg >= 0 && ctx->gemm_cfg < kNumCfgs) return ctx->gemm_cfg;
-  return 2;
+  return 0;
 }
 
 template <int MODE>
 hipError_t launch_mode(const nova_ctx* ctx, hipStream_t st, const bf16_t* A, const bf16_t* W, int M, int Nout,
                        int K, const EpiParams<bf16_t>& ep) {
-  switch (pick_cfg(ctx, M, Nout)) {
-    case 0: return launch_cfg<256, 256, 2, 4, 64, 2, MODE>(st, A, W, M, Nout, K, ep);
-    case 1: return launch_cfg<256, 256, 2, 4, 32, 4, MODE>(st, A, W, M, Nout, K, ep);
-    case 2: return launch_cfg<128, 128, 2, 2, 64, 2, MODE>(st, A, W, M, Nout, K, ep);
-    case 3: return launch_cfg<128, 128, 2, 2, 32, 4, MODE>(st, A, W, M, Nout, K, ep);
-    case 4: return launch_cfg<128, 128, 2, 2, 64, 4, MODE>(st, A, W, M, Nout, K, ep);
-    default: return launch_cfg<256, 128, 4, 2, 64, 3, MODE>(st, A, W, M, Nout, K, ep);
+  switch (pick_cfg(ctx)) {
+    case 1: return launch_cfg<256, 256, 2, 4, 64, 2, MODE>(st, A, W, M, Nout, K, ep);
+    case 2: return launch_cfg<256, 128, 4, 2, 64, 3, MODE>(st, A, W, M, Nout, K, ep);
+    default: return launch_cfg<128, 128, 2, 2, 64, 2, MODE>(st, A, W, M, Nout, K, ep);
   }
 }
 

@@ -48,7 +48,7 @@ struct StageTimer {
 };
 
 // entropy.hip
-hipError_t launch_entropy(hipStream_t st, const void* logits, int dtype, int64_t rows_per_batch,
+hipError_t launch_entropy(hipStream_t st, int num_cus, const void* logits, int dtype, int64_t rows_per_batch,
                           int batch, int V, int64_t stride, float* H, float* mean);
 // select.hip
 hipError_t launch_select(hipStream_t st, const float* H, int B, int N, int k, const int32_t* k_per_row,
