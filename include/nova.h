@@ -57,7 +57,7 @@ typedef struct nova_block_shape {
 
 /* Block weights, device pointers, same dtype as the activations.  Matrices are
  * stored out-feature major: W[out][in], so a projection is y = u * W^T + b.
- * Biases may be NULL (treated as zero). */
+ * Biases may be NULL (treated as zero).  Every non-NULL pointer must be 16-byte aligned. */
 typedef struct nova_block_weights {
   const void* w_qkv; /* [3C, C]  rows 0..C-1 query, C..2C-1 key, 2C..3C-1 value */
   const void* b_qkv; /* [3C]                                                     */

@@ -178,9 +178,10 @@ int nova_pruned_block(nova_ctx* ctx, void* stream, const nova_block_shape* shape
   if (shape->k == 0 || shape->B == 0) return NOVA_OK;
   if (!x || !kept_idx || !k_cache || !v_cache || !y_kept) return NOVA_ERR_INVALID_ARG;
   if (!weights->w_qkv || !weights->w_o || !weights->w_fc1 || !weights->w_fc2) return NOVA_ERR_INVALID_ARG;
-  const void* ptrs[] = {x, k_cache, v_cache, y_kept, weights->w_qkv, weights->w_o, weights->w_fc1, weights->w_fc2};
+  const void* ptrs[] = {x, k_cache, v_cache, y_kept, weights->w_qkv, weights->w_o, weights->w_fc1, weights->w_fc2,
+                        weights->b_qkv, weights->b_o, weights->b_fc1, weights->b_fc2};
   for (const void* p : ptrs)
-    if (!aligned16(p)) return NOVA_ERR_INVALID_ARG;
+    if (p && !aligned16(p)) return NOVA_ERR_INVALID_ARG;
   const size_t need = carve_workspace(*shape, nullptr).total;
   if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
     return NOVA_ERR_WORKSPACE;

@@ -26,7 +26,22 @@ struct EpiParams {
   int Ntok;
 };
 
-__device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)); }
+// Exact-form GELU 0.5 v (1 + erf(v / sqrt 2)).  erf through the rational approximation 7.1.26 of
+// Abramowitz & Stegun (|error| <= 1.5e-7, far below the bf16 / fp32 rounding of the result) on the
+// native reciprocal and exp2 units instead of the branchy library erff: this runs once per output
+// element of the FFN up-projection.
+__device__ __forceinline__ float gelu_erf(float v) {
+  const float x = fabsf(v) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+  float poly = fmaf(1.061405429f, t, -1.453152027f);
+  poly = fmaf(poly, t, 1.421413741f);
+  poly = fmaf(poly, t, -0.284496736f);
+  poly = fmaf(poly, t, 0.254829592f);
+  poly *= t;
+  const float e = __builtin_amdgcn_exp2f(-x * x * 1.4426950408889634f);
+  const float erf_abs = fmaf(-poly, e, 1.0f);               // erf(|v| / sqrt 2)
+  return 0.5f * v * (1.0f + copysignf(erf_abs, v));
+}
 
 template <typename T, int MODE>
 __device__ __forceinline__ void epilogue_store(const EpiParams<T>& p, int row, int col, float acc) {

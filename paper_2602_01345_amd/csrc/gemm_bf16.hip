@@ -152,7 +152,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
   auto mfmas = [&](int buf, int lo, int hi) {
 #pragma unroll
     for (int t = 0; t < TM * TN; ++t)
-      if (t >= lo && t < hi) acc[t / TN][t % TN] = mfma32(a[buf][t / TN], b[buf][t % TN], acc[t / TN][t % TN]);
+      if (t >= lo && t < hi) acc[t / TN][t % TN] = mfma32(b[buf][t % TN], a[buf][t / TN], acc[t / TN][t % TN]);
   };
   constexpr int LEAD = 1;                   // MFMAs issued before the next K step's LDS reads
   static_assert(KS % 2 == 0, "fragment buffers alternate per K step");
@@ -189,72 +189,98 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
     fill = fill + 1 == NST ? 0 : fill + 1;
   }
   // ---- epilogue, stage 1: accumulators (+ bias, GELU) -> bf16 tile in LDS, row-major --------
-  // lane owns column l % 32 of each MFMA tile and rows 8*(r/4) + 4*(l/32) + r%4
+  // The MFMAs ran with the weight rows as the A operand, so a lane owns token l % 32 of each MFMA
+  // tile and, per register group r / 4, four consecutive output features: one 8-byte LDS write.
   bf16_t* ct = reinterpret_cast<bf16_t*>(lds);
 #pragma unroll
-  for (int jn = 0; jn < TN; ++jn) {
-    const int lc = wn * (BN / WN) + jn * 32 + r32;
-    const int col = n0 + lc;
-    const float bias = (ep.bias && col < Nout) ? (float)ep.bias[col] : 0.0f;
+  for (int jn = 0; jn < TN; ++jn)
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const int lc = wn * (BN / WN) + jn * 32 + 8 * g4 + 4 * half;   // first of 4 consecutive features
+      const int col = n0 + lc;
+      float bias[4] = {0.f, 0.f, 0.f, 0.f};
+      if (ep.bias && col < Nout) {
+        const bf16x4 bv = *reinterpret_cast<const bf16x4*>(ep.bias + col);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int lrw = wm * (BM / WM) + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        float v = acc[i][jn][r] + bias;
-        if (MODE == EPI_GELU) v = gelu_erf(v);
-        ct[lrw * CT_PITCH + lc] = (bf16_t)v;
+        for (int e = 0; e < 4; ++e) bias[e] = (float)bv[e];
       }
-  }
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int lrw = wm * (BM / WM) + i * 32 + r32;
+        bf16x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float v = acc[i][jn][g4 * 4 + e] + bias[e];
+          if (MODE == EPI_GELU) v = gelu_erf(v);
+          o[e] = (bf16_t)v;
+        }
+        *reinterpret_cast<bf16x4*>(ct + lrw * CT_PITCH + lc) = o;
+      }
+    }
   __syncthreads();
 
   // ---- stage 2: 16-byte row chunks out of LDS, coalesced global stores ----------------------
+  // A thread keeps one column chunk and walks down the tile rows, so everything that depends on
+  // the column (q / key / value split, head, channel) is computed once.
+  constexpr int NT = NW * 64;
   constexpr int CPR = BN / 8;                       // chunks per tile row
-  for (int c = tid; c < BM * CPR; c += NW * 64) {
-    const int lrw = c / CPR, cc = c - lrw * CPR;
-    const int row = m0 + lrw, col = n0 + cc * 8;
-    if (row >= M || col >= Nout) continue;
-    bf16x8 v = *reinterpret_cast<const bf16x8*>(ct + lrw * CT_PITCH + cc * 8);
+  constexpr int RPP = NT / CPR;                     // tile rows covered per pass
+  static_assert(NT % CPR == 0 && BM % RPP == 0, "chunk walk tiles the output tile");
+  {
+    const int cc = tid % CPR, r_first = tid / CPR;
+    const int col = n0 + cc * 8;
+    int sel = 0, cf = col, head = 0, d = 0;
     if (MODE == EPI_QKV) {
-      const int sel = col / ep.C, cf = col - sel * ep.C;
-      if (sel == 0) {
-        *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + cf) = v;
-      } else if (sel == 1) {
-        const int bb = row / ep.k, s = row - bb * ep.k;
-        const int head = cf / ep.dh, d = cf - head * ep.dh;
-        *reinterpret_cast<bf16x8*>(ep.kc + (((int64_t)bb * ep.heads + head) * ep.cap + ep.P + s) * ep.dh + d) = v;
-      }
-    } else if (MODE == EPI_GELU) {
-      *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + col) = v;
-    } else {
-      int64_t rrow = row;
-      int64_t rpitch = ep.ldo;
-      if (MODE == EPI_ATTN_OUT) {
-        const int bb = row / ep.k;
-        rrow = (int64_t)bb * ep.Ntok + min(max(ep.idx[row], 0), ep.Ntok - 1);
-        rpitch = ep.C;
-      }
-      const bf16x8 rs = *reinterpret_cast<const bf16x8*>(ep.res + rrow * rpitch + col);
-      bf16x8 o;
+      sel = col / ep.C; cf = col - sel * ep.C;
+      head = cf / ep.dh; d = cf - head * ep.dh;
+    }
+    if (col < Nout && !(MODE == EPI_QKV && sel == 2)) {
+      for (int lrw = r_first; lrw < BM; lrw += RPP) {
+        const int row = m0 + lrw;
+        if (row >= M) break;
+        const bf16x8 v = *reinterpret_cast<const bf16x8*>(ct + lrw * CT_PITCH + cc * 8);
+        if (MODE == EPI_QKV) {
+          if (sel == 0) {
+            *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + cf) = v;
+          } else {
+            const int bb = row / ep.k, s = row - bb * ep.k;
+            *reinterpret_cast<bf16x8*>(ep.kc + (((int64_t)bb * ep.heads + head) * ep.cap + ep.P + s) * ep.dh + d) = v;
+          }
+        } else if (MODE == EPI_GELU) {
+          *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + col) = v;
+        } else {
+          int64_t rrow = row;
+          int64_t rpitch = ep.ldo;
+          if (MODE == EPI_ATTN_OUT) {
+            const int bb = row / ep.k;
+            rrow = (int64_t)bb * ep.Ntok + min(max(ep.idx[row], 0), ep.Ntok - 1);
+            rpitch = ep.C;
+          }
+          const bf16x8 rs = *reinterpret_cast<const bf16x8*>(ep.res + rrow * rpitch + col);
+          bf16x8 o;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] = (bf16_t)((float)v[e] + (float)rs[e]);
-      *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + col) = o;
+          for (int e = 0; e < 8; ++e) o[e] = (bf16_t)((float)v[e] + (float)rs[e]);
+          *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + col) = o;
+        }
+      }
     }
   }
   if (MODE == EPI_QKV) {
-    // value columns: the cache is key-minor, so walk the tile column by column with the lanes
-    // along the rows (consecutive tokens -> consecutive addresses)
+    // value columns: the cache is key-minor, so a thread keeps one tile row (token) and walks
+    // the value columns; consecutive lanes hold consecutive tokens -> consecutive addresses
     const int v_lo = max(2 * ep.C - n0, 0);          // first tile column that is a value feature
-    const int ncol = min(BN, Nout - n0) - v_lo;
-    if (ncol > 0) {
-      for (int e = tid; e < BM * ncol; e += NW * 64) {
-        const int lc = v_lo + e / BM, lrw = e % BM;
-        const int row = m0 + lrw;
-        if (row >= M) continue;
-        const int cf = n0 + lc - 2 * ep.C;
+    const int v_hi = min(BN, Nout - n0);
+    if (v_hi > v_lo) {
+      constexpr int CG = NT / BM;                    // column groups walked in parallel
+      static_assert(NT % BM == 0, "one thread per tile row and column group");
+      const int lrw = tid % BM, cg = tid / BM;
+      const int row = m0 + lrw;
+      if (row < M) {
         const int bb = row / ep.k, s = row - bb * ep.k;
-        const int head = cf / ep.dh, d = cf - head * ep.dh;
-        ep.vc[(((int64_t)bb * ep.heads + head) * ep.dh + d) * ep.cap + ep.P + s] = ct[lrw * CT_PITCH + lc];
+        bf16_t* vrow = ep.vc + (int64_t)bb * ep.heads * ep.dh * ep.cap + ep.P + s;
+        const int cf0 = n0 - 2 * ep.C;               // value feature of tile column 0
+        for (int lc = v_lo + cg; lc < v_hi; lc += CG)
+          vrow[(int64_t)(cf0 + lc) * ep.cap] = ct[lrw * CT_PITCH + lc];   // (head * dh + d) * cap
       }
     }
   }
