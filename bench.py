@@ -243,6 +243,23 @@ def main():
                                                      st.y_kept, st.kept_idx, st.keep_mask, st.cache_prev, st.out,
                                                      st.cache_new) for st in blocks])
 
+        # the layer-linkage ratio kernel sits between entropy and select: a latency-bound launch
+        # (B rows), reported as time per launch over one launch per block
+        cm = torch.rand(wl.B, device="cuda") * 5.0 + 1.0
+        cs = torch.zeros(wl.B, device="cuda")
+        cr = torch.full((wl.B,), 0.5, device="cuda")
+        co = torch.empty(wl.B, device="cuda")
+        ck = torch.empty(wl.B, dtype=torch.int32, device="cuda")
+        run_ratio = lambda: [nova.layer_ratio(cm, cs, cr, j + 1, scale.N, co, ck) for j in range(len(blocks))]
+        run_ratio()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        run_ratio()
+        e1.record()
+        torch.cuda.synchronize()
+        hbm["layer_ratio"] = {"us_per_launch": round(e0.elapsed_time(e1) * 1e3 / len(blocks), 2), "bound": "latency"}
+
     traffic = None
     tf = os.path.join(ROOT, "profiles", f"attention_{args.config}_hbm_traffic.txt")
     if os.path.exists(tf):

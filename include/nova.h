@@ -166,6 +166,40 @@ int nova_merge_cache(nova_ctx* ctx, void* stream, int dtype, int B, int C, int h
                      const uint8_t* keep_mask, const void* cache_prev, void* out, void* cache_new);
 
 /*
+ * Ratio controllers (Sec. 3.3, "Adaptive Acceleration Activation" and "Dual-Linkage
+ * Acceleration").  The first two are host arithmetic on one instance's scale mean entropies
+ * (no GPU work, ctx-free); the third runs on the device so that a layer's keep counts reach
+ * nova_select (its k_per_row argument) without a host round trip.
+ *
+ * nova_activation_scale: with g_t = Hbar_t - Hbar_{t-1}, eta = mean of g_2..g_{t_est} and
+ * g~_t = (g_t + g_{t-1}) / 2, *t_star is the earliest t >= t_est + 1 (1-based) with
+ * g~_t <= alpha * eta among the scales given, or 0 when there is none (yet); acceleration
+ * starts at scale t* + 1.  Appending later scales never changes a detected t*.
+ *   hbar   HOST double [T]: Hbar_1 .. Hbar_T; T >= 0, t_est >= 2
+ */
+int nova_activation_scale(const double* hbar, int T, int t_est, double alpha, int* t_star);
+
+/* Scale-linkage ratio: *ratio = sigmoid((t - (t_star + 1)) / tau) - lambda * tanh(g_t)
+ * (host scalars; tau != 0).  Not clamped. */
+int nova_scale_ratio(int t, int t_star, double g_t, double tau, double lambda, double* ratio);
+
+/*
+ * Layer-linkage ratio and keep counts of layer j (1-based) for every batch row, in fp32:
+ *   mu        = entropy_sum[b] / (j - 1)                       (j >= 2)
+ *   ratio_tj  = ratio_t[b] - ((mean_entropy[b] - mu) / mu) * ratio_t[b]
+ *               (= ratio_t[b] when j == 1 or mu == 0)
+ *   k_per_row = N - floor(clamp(ratio_tj, 0, 1) * N)           (a NaN ratio keeps all N)
+ *   entropy_sum[b] <- (j == 1 ? 0 : entropy_sum[b]) + mean_entropy[b]
+ *   mean_entropy  DEVICE fp32 [B]  this layer's scale mean entropy (nova_entropy's mean output)
+ *   entropy_sum   DEVICE fp32 [B]  in/out: sum over the preceding layers of this scale
+ *   ratio_t       DEVICE fp32 [B]  scale-linkage ratio of each row
+ *   ratio_tj      out DEVICE fp32 [B], not clamped; k_per_row out DEVICE int32 [B]
+ * 0 <= N <= 2^24.  B == 0 is a no-op.
+ */
+int nova_layer_ratio(nova_ctx* ctx, void* stream, const float* mean_entropy, float* entropy_sum,
+                     const float* ratio_t, int j, int B, int N, float* ratio_tj, int32_t* k_per_row);
+
+/*
  * Instrumentation (not part of the hot path): per-kernel device timing with HIP events on
  * the caller's stream.  While a stage's bit is set in `stage_mask`, every launch of that
  * stage by the four entry points is bracketed by a pair of events (created on the host as

@@ -9,7 +9,7 @@ from __future__ import annotations
 import ctypes as C
 import os
 from dataclasses import dataclass
-from typing import Dict, Optional
+from typing import Dict, Optional, Sequence
 
 import torch
 
@@ -82,10 +82,13 @@ def load_library() -> C.CDLL:
     lib.nova_merge_cache.argtypes = [vp, vp, i32] + [i32] * 7 + [vp] * 7
     lib.nova_profile_stages.argtypes = [vp, C.c_uint32]
     lib.nova_profile_collect.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.nova_activation_scale.argtypes = [C.POINTER(C.c_double), i32, i32, C.c_double, C.POINTER(i32)]
+    lib.nova_scale_ratio.argtypes = [i32, i32, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_double)]
+    lib.nova_layer_ratio.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp]
     lib.nova_profile_stages.restype = i32
     lib.nova_profile_collect.restype = i32
     for f in (lib.nova_create, lib.nova_destroy, lib.nova_entropy, lib.nova_select, lib.nova_pruned_block,
-              lib.nova_merge_cache):
+              lib.nova_merge_cache, lib.nova_activation_scale, lib.nova_scale_ratio, lib.nova_layer_ratio):
         f.restype = i32
     _LIB = lib
     return lib
@@ -108,6 +111,27 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
 
 def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
+
+
+def activation_scale(hbar: Sequence[float], t_est: int, alpha: float) -> int:
+    """nova_activation_scale: t* (1-based) for the scale mean entropies seen so far, 0 if none (host only)."""
+    lib = load_library()
+    arr = (C.c_double * max(len(hbar), 1))(*[float(h) for h in hbar])
+    out = C.c_int(0)
+    rc = lib.nova_activation_scale(arr, len(hbar), int(t_est), float(alpha), C.byref(out))
+    if rc != 0:
+        raise NovaError(rc, "nova_activation_scale")
+    return out.value
+
+
+def scale_ratio(t: int, t_star: int, g_t: float, tau: float, lam: float) -> float:
+    """nova_scale_ratio: the scale-linkage reduction ratio (host only)."""
+    lib = load_library()
+    out = C.c_double(0.0)
+    rc = lib.nova_scale_ratio(int(t), int(t_star), float(g_t), float(tau), float(lam), C.byref(out))
+    if rc != 0:
+        raise NovaError(rc, "nova_scale_ratio")
+    return out.value
 
 
 class Nova:
@@ -149,6 +173,17 @@ class Nova:
         self._check(self.lib.nova_profile_collect(self.ctx, int(stage), C.byref(ms), C.byref(n)),
                     "nova_profile_collect")
         return ms.value, n.value
+
+    # -- nova_layer_ratio -----------------------------------------------------------
+    def layer_ratio(self, mean_entropy: torch.Tensor, entropy_sum: torch.Tensor, ratio_t: torch.Tensor, j: int,
+                    N: int, ratio_tj: torch.Tensor, k_per_row: torch.Tensor):
+        """Per-row layer-linkage ratio and keep counts of layer j (1-based); entropy_sum is updated in place."""
+        B = mean_entropy.shape[0]
+        assert k_per_row.dtype == torch.int32 and all(t.dtype == torch.float32 for t in
+                                                      (mean_entropy, entropy_sum, ratio_t, ratio_tj))
+        rc = self.lib.nova_layer_ratio(self.ctx, _stream(), _ptr(mean_entropy), _ptr(entropy_sum), _ptr(ratio_t),
+                                       int(j), B, int(N), _ptr(ratio_tj), _ptr(k_per_row))
+        self._check(rc, "nova_layer_ratio")
 
     # -- nova_entropy ---------------------------------------------------------------
     def entropy(self, logits: torch.Tensor, entropy: torch.Tensor, mean: Optional[torch.Tensor] = None):

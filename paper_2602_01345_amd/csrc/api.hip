@@ -170,6 +170,18 @@ int nova_select(nova_ctx* ctx, void* stream, const float* entropy, int B, int N,
   return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
 }
 
+int nova_layer_ratio(nova_ctx* ctx, void* stream, const float* mean_entropy, float* entropy_sum,
+                     const float* ratio_t, int j, int B, int N, float* ratio_tj, int32_t* k_per_row) {
+  if (!ctx) return NOVA_ERR_INVALID_ARG;
+  if (j < 1 || B < 0 || N < 0 || N > (1 << 24)) return NOVA_ERR_INVALID_ARG;
+  if (B == 0) return NOVA_OK;
+  if (!mean_entropy || !entropy_sum || !ratio_t || !ratio_tj || !k_per_row) return NOVA_ERR_INVALID_ARG;
+  if (int rc = set_device(ctx)) return rc;
+  hipError_t e = launch_layer_ratio(static_cast<hipStream_t>(stream), mean_entropy, entropy_sum, ratio_t, j, B, N,
+                                    ratio_tj, k_per_row);
+  return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
+}
+
 int nova_pruned_block(nova_ctx* ctx, void* stream, const nova_block_shape* shape,
                       const nova_block_weights* weights, const void* x, const int32_t* kept_idx, void* k_cache,
                       void* v_cache, void* y_kept, void* workspace, size_t workspace_bytes) {

@@ -51,6 +51,8 @@ struct StageTimer {
 hipError_t launch_entropy(hipStream_t st, int num_cus, const void* logits, int dtype, int64_t rows_per_batch,
                           int batch, int V, int64_t stride, float* H, float* mean);
 // select.hip
+hipError_t launch_layer_ratio(hipStream_t st, const float* mean_entropy, float* entropy_sum, const float* ratio_t,
+                              int j, int B, int N, float* ratio_tj, int32_t* k_per_row);
 hipError_t launch_select(hipStream_t st, const float* H, int B, int N, int k, const int32_t* k_per_row,
                          int32_t* idx, uint8_t* mask);
 // merge.hip

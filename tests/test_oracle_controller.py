@@ -197,3 +197,12 @@ def test_keep_count_is_ceil_of_kept_fraction(N):
     for num in range(0, 65):
         r = Fraction(num, 64)
         assert K.keep_count(float(r), N) == math.ceil((1 - r) * N)
+
+
+@pytest.mark.parametrize("N", [7, 169, 4096, 65536])
+def test_keep_count_f32_agrees_where_the_product_is_exact(N):
+    # ratios num/64 are exact in fp32 and so is num/64 * N for these N: both decisions coincide
+    for num in range(0, 65):
+        assert K.keep_count_f32(num / 64.0, N) == K.keep_count(num / 64.0, N)
+    assert K.keep_count_f32(float("nan"), N) == N
+    assert K.keep_count_f32(-2.0, N) == N and K.keep_count_f32(3.0, N) == 0
