@@ -109,6 +109,62 @@ def cpu_baseline(hb, wl, scale, k):
                       f"in float64 NumPy, {dt:.1f} s"}
 
 
+def image_chain(nova, wl, weights, gen):
+    """All scales of the workload's grid list for one batch of images: dense up to the scale before the
+    first pruned one (which also builds the residual caches), then the pruned scales with the workload's
+    keep table.  Inputs of every scale (hidden states, logits) are generated on the device beforehand."""
+    import torch
+    import workloads as WL
+    from paper_2602_01345_amd.image import ImageRunner
+    grids = WL.grid_list(wl)
+    first_pruned = grids.index(wl.scales[0].grid)
+    dtype = WL.torch_dtype(wl.dtype)
+    runner = ImageRunner(nova, B=wl.B, C=wl.C, heads=wl.heads, grids=grids, dtype=dtype, weights=weights,
+                         ffn_mult=wl.ffn_mult)
+    xs = [torch.randn((wl.B, g * g, wl.C), generator=gen, device="cuda").to(dtype) for g in grids]
+    # logits of the pruned scales (one tensor per block); the dense scales need none
+    logits = {}
+    for t in range(first_pruned, len(grids)):
+        N = grids[t] * grids[t]
+        logits[t] = [(torch.randn((wl.B, N, wl.V), generator=gen, device="cuda") * 3.0).to(dtype) for _ in range(wl.L)]
+    tables = {t: [WL.keep_count(wl.keep_ratio(j), grids[t] * grids[t]) for j in range(wl.L)]
+              for t in range(first_pruned, len(grids))}
+
+    plans = runner.plan_image(tables, logits, first_cache_scale=first_pruned - 1)
+    for p, x in zip(plans, xs):
+        p.x.copy_(x)
+    del xs
+
+    def time_image(reps):
+        ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in grids]
+              for _ in range(reps)]
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for r in range(reps):
+            for t, p in enumerate(plans):
+                ev[r][t][0].record()
+                runner.launch(p)
+                ev[r][t][1].record()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        per_scale = [round(sum(ev[r][t][0].elapsed_time(ev[r][t][1]) for r in range(reps)) / reps, 3)
+                     for t in range(len(grids))]
+        return ms, per_scale
+
+    time_image(1)                                        # warm-up, launches issued one by one
+    eager_ms, eager_scales = time_image(2)
+    for p in plans:
+        runner.capture(p)                                # one HIP graph per scale
+    time_image(1)
+    graph_ms, graph_scales = time_image(3)
+    return {"grids": grids, "first_pruned_grid": grids[first_pruned],
+            "ms_per_image": round(graph_ms / wl.B, 3), "ms_per_batch": round(graph_ms, 3), "ms_per_scale": graph_scales,
+            "launched_one_by_one": {"ms_per_batch": round(eager_ms, 3), "ms_per_scale": eager_scales},
+            "note": "one HIP graph per scale; dense scales keep every token; pruned scales use the workload's "
+                    "keep table; synthetic inputs"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -117,6 +173,9 @@ def main():
     ap.add_argument("--config", default="cfg5", help="cfg2..cfg5 (default: the largest, cfg5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stage-pass", action="store_true")
+    ap.add_argument("--image", action="store_true",
+                    help="also time the chained multi-scale run (all scales of the config's grid list) and "
+                         "report ms per image")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (known HBM traffic) for scaling rocprofv3 byte counters")
     args = ap.parse_args()
@@ -282,6 +341,8 @@ def main():
         "kernels": kernels,
         "hbm_kernels_sustained": hbm,
     }
+    if args.image:
+        out["image_chain"] = image_chain(nova, wl, [st.weights for st in runner.blocks], gen)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(hb0, wl, scale, ks[0])
     print(json.dumps(out))

@@ -40,7 +40,7 @@ __device__ __forceinline__ int swz(int r, int c) {
   return r * 64 + ((c ^ ((r >> 2) & 3)) << 4);
 }
 
-template <int BM, int BN, int WM, int WN, int BK, int NST, int MODE>
+template <int BM, int BN, int WM, int WN, int BK, int NST, bool STAGGER, int MODE>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __restrict__ A,
                                                                 const bf16_t* __restrict__ W, int M, int Nout,
                                                                 int K, int tiles_m, int tiles_n,
@@ -118,10 +118,16 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
       for (int r = 0; r < 16; ++r) acc[i][jn][r] = 0.f;
 
   const int KT = K / BK;
+  // With few rows every tile column is streamed by one workgroup (or a few that share it), and all
+  // of them would walk K in step: the same 128-byte slice of every weight row at the same time,
+  // rows a power-of-two stride apart, i.e. a handful of memory channels.  Each tile column
+  // therefore starts its (cyclic) walk over K at its own offset.
+  const int kt_first = STAGGER ? (int)(((int64_t)tn * KT) / tiles_n) : 0;
+  auto k_of = [&](int t) { const int q = t + kt_first; return (q >= KT ? q - KT : q) * BK; };
   // prologue: NST-1 tiles in flight, wait for the first
 #pragma unroll
   for (int t = 0; t < NST - 1; ++t)
-    if (t < KT) issue(t, t * BK, 0, LPW);
+    if (t < KT) issue(t, k_of(t), 0, LPW);
   if (KT >= NST - 1) { WAIT_VMCNT((NST - 2) * LPW); } else { WAIT_VMCNT(0); }
   __syncthreads();
 
@@ -167,7 +173,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
     for (int ks = 0; ks < KS - 1; ++ks) {
       mfmas(ks & 1, 0, LEAD);
       __builtin_amdgcn_sched_barrier(0);
-      if (more) issue(fill, (kt + NST - 1) * BK, ks * LPS, ks + 2 == KS ? LPW : (ks + 1) * LPS);
+      if (more) issue(fill, k_of(kt + NST - 1), ks * LPS, ks + 2 == KS ? LPW : (ks + 1) * LPS);
       read_frags((ks + 1) & 1, stage, ks + 1);
       __builtin_amdgcn_sched_barrier(0);
       mfmas(ks & 1, LEAD, TM * TN);
@@ -177,7 +183,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
     // the current stage must be complete before anyone may refill it
     if (more) { WAIT_VMCNT((NST - 2) * LPW); } else { WAIT_VMCNT(0); }
     __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0)
-    __syncthreads();
+    // a bare barrier: __syncthreads() would add a wait for ALL outstanding loads, i.e. also for the
+    // tiles requested for later iterations, and a ring deeper than two stages would gain nothing
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
     const int next = stage + 1 == NST ? 0 : stage + 1;
     mfmas((KS - 1) & 1, 0, LEAD);
     __builtin_amdgcn_sched_barrier(0);
@@ -286,36 +298,67 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
   }
 }
 
-template <int BM, int BN, int WM, int WN, int BK, int NST, int MODE>
+template <int BM, int BN, int WM, int WN, int BK, int NST, bool STAGGER, int MODE>
 hipError_t launch_cfg(hipStream_t st, const bf16_t* A, const bf16_t* W, int M, int Nout, int K,
                       const EpiParams<bf16_t>& ep) {
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (Nout + BN - 1) / BN;
-  gemm_bf16_kernel<BM, BN, WM, WN, BK, NST, MODE><<<tiles_m * tiles_n, WM * WN * 64, 0, st>>>(
+  gemm_bf16_kernel<BM, BN, WM, WN, BK, NST, STAGGER, MODE><<<tiles_m * tiles_n, WM * WN * 64, 0, st>>>(
       A, W, M, Nout, K, tiles_m, tiles_n, ep);
   return hipGetLastError();
 }
 
 // Tile configurations (NOVA_GEMM_CFG forces one, for tuning):
-//   0: 128x128x64, 4 waves of 64x64, 2 LDS stages, two workgroups per CU   (default)
-//   1: 256x256x64, 8 waves of 128x64, 2 LDS stages, one workgroup per CU
-//   2: 256x128x64, 8 waves of 64x64, 3 LDS stages, one workgroup per CU
-// Measured on MI355X at the workloads' shapes (M = 1.6k..4.9k, N, K = 2k..8k) the first one wins:
-// two independent workgroups per CU overlap one tile's prologue / epilogue with the other's MFMAs
-// and quantise better over the 256 CUs.
-constexpr int kNumCfgs = 3;
+//   0: 128x128x64, 4 waves of 64x64, 2 LDS stages, two workgroups per CU
+//   1: 256x256x64, 8 waves of 128x64, 2 stages
+//   2: 256x128x64, 8 waves of 64x64, 3 stages
+//   3: 64x32x64, 2 waves of 32x32, 6 stages, staggered K walk          (M <= 64)
+//   4: 128x32x64, 4 waves of 32x32, 4 stages, staggered K walk         (M <= 512)
+//   5: 128x128x64, 4 waves, 3 stages, one workgroup per CU
+//   6: 256x256x32, 8 waves of 128x64, 3 stages
+// Without a forced choice the launcher prices the candidates 2, 5 and 6 with a small model fitted
+// to measurements on MI355X (M = 1.6k..4.9k, N and K = 2k..8k): a launch takes
+// ceil(tiles / CUs) rounds, a round costs the tile's flops at the rate one workgroup sustains when
+// every CU holds one, plus a fixed prologue/epilogue time.  Large tiles win when their tile count
+// fills whole rounds; the one-workgroup 128x128 kernel wins when there are few tiles (narrow
+// outputs, late blocks with few kept tokens).
+constexpr int kNumCfgs = 7;
 
-int pick_cfg(const nova_ctx* ctx) {
+struct Candidate {
+  int cfg, bm, bn;
+  double rate;   // flop/s of one resident workgroup with all CUs busy
+};
+
+int pick_cfg(const nova_ctx* ctx, int M, int Nout, int K) {
   if (ctx && ctx->gemm_cfg >= 0 && ctx->gemm_cfg < kNumCfgs) return ctx->gemm_cfg;
-  return 0;
+  // few rows (the early, small scales): the weights are streamed once and the output has too few
+  // large tiles to occupy the CUs, so narrow tiles spread the weight stream over many workgroups
+  if (M <= 64) return 3;
+  if (M <= 512) return 4;
+  static const Candidate cands[] = {{2, 256, 128, 3.3e12}, {5, 128, 128, 3.2e12}, {6, 256, 256, 3.6e12}};
+  const double slots = ctx ? ctx->num_cus : 256;
+  const double t_fixed = 8e-6;
+  int best = 2;
+  double best_t = 1e30;
+  for (const Candidate& c : cands) {
+    const double tiles = (double)((M + c.bm - 1) / c.bm) * ((Nout + c.bn - 1) / c.bn);
+    const double rounds = std::ceil(tiles / slots);
+    const double t = rounds * (2.0 * c.bm * c.bn * K / c.rate + t_fixed);
+    if (t < best_t) { best_t = t; best = c.cfg; }
+  }
+  return best;
 }
 
 template <int MODE>
 hipError_t launch_mode(const nova_ctx* ctx, hipStream_t st, const bf16_t* A, const bf16_t* W, int M, int Nout,
                        int K, const EpiParams<bf16_t>& ep) {
-  switch (pick_cfg(ctx)) {
-    case 1: return launch_cfg<256, 256, 2, 4, 64, 2, MODE>(st, A, W, M, Nout, K, ep);
-    case 2: return launch_cfg<256, 128, 4, 2, 64, 3, MODE>(st, A, W, M, Nout, K, ep);
-    default: return launch_cfg<128, 128, 2, 2, 64, 2, MODE>(st, A, W, M, Nout, K, ep);
+  switch (pick_cfg(ctx, M, Nout, K)) {
+    case 0: return launch_cfg<128, 128, 2, 2, 64, 2, false, MODE>(st, A, W, M, Nout, K, ep);
+    case 1: return launch_cfg<256, 256, 2, 4, 64, 2, false, MODE>(st, A, W, M, Nout, K, ep);
+    case 3: return launch_cfg<64, 32, 2, 1, 64, 6, true, MODE>(st, A, W, M, Nout, K, ep);
+    case 4: return launch_cfg<128, 32, 4, 1, 64, 4, true, MODE>(st, A, W, M, Nout, K, ep);
+    case 5: return launch_cfg<128, 128, 2, 2, 64, 3, false, MODE>(st, A, W, M, Nout, K, ep);
+    case 6: return launch_cfg<256, 256, 2, 4, 32, 3, false, MODE>(st, A, W, M, Nout, K, ep);
+    default: return launch_cfg<256, 128, 4, 2, 64, 3, false, MODE>(st, A, W, M, Nout, K, ep);
   }
 }
 

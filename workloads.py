@@ -103,6 +103,15 @@ def _scales(grids: List[int], first_pruned: int) -> Tuple[Scale, ...]:
     return tuple(out)
 
 
+def grid_list(wl: "Workload") -> List[int]:
+    """The full list of scale grids the workload's pruned scales belong to."""
+    last = wl.scales[-1]
+    for grids in (_G256, _G512, _G1024):
+        if last.grid in grids and last.kv_len == _prefix(grids, grids.index(last.grid)):
+            return list(grids)
+    raise ValueError("the workload's scales match no known grid list")
+
+
 WORKLOADS: Dict[str, Workload] = {
     "cfg1": Workload("cfg1-tiny-f32", "f32", B=1, C=64, heads=4, L=1, V=512,
                      keep_hi=0.5, keep_lo=0.5, scales=_scales(_G256, 16)),
