@@ -10,7 +10,7 @@
 // so the online-softmax state (running max and sum) is one scalar per lane and query group, and
 // no data is exchanged between lanes except one max/sum swap between the two half-waves.
 //
-// A workgroup is 4 waves; a wave owns NQ groups of 32 queries (every K / V fragment read from LDS
+// A workgroup is NW (4 or 8) waves; a wave owns NQ groups of 32 queries (every K / V fragment read from LDS
 // feeds NQ MFMAs).  K and V tiles of 64 keys stream through an NST-stage LDS ring filled by
 // direct global->LDS loads; the bank-conflict XOR swizzle is applied on the global side of those
 // loads.  Workgroup ids are remapped so that all query blocks of one (batch row, head) run on the
@@ -51,8 +51,8 @@ __device__ __forceinline__ int swz(int r, int c) {
   return r * 128 + ((c ^ ((r >> 1) & 7)) << 4);
 }
 
-template <int DH, int NQ, int NST, int OCC>
-__global__ __launch_bounds__(ATT_WAVES * 64, OCC) void attention_bf16_kernel(
+template <int DH, int NQ, int NST, int OCC, int NW>
+__global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc, int k, int C,
     int heads, int cap, int kv_total, int nqb, int nsplit, int64_t part_rows, float scale_log2,
     bf16_t* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml) {
@@ -64,10 +64,10 @@ __global__ __launch_bounds__(ATT_WAVES * 64, OCC) void attention_bf16_kernel(
   constexpr int KSTEPS = DH / 16;                // MFMAs along dh for S^T
   constexpr int DB = DH / 32;                    // 32-row blocks of O^T
   constexpr int K_RPI = 1024 / KROWB;            // K rows filled per wave load instruction
-  constexpr int LK = BKV / K_RPI / ATT_WAVES;    // K load instructions per wave per tile
-  constexpr int LV = DH / 8 / ATT_WAVES;         // V load instructions per wave per tile (8 rows each)
+  constexpr int LK = BKV / K_RPI / NW;    // K load instructions per wave per tile
+  constexpr int LV = DH / 8 / NW;         // V load instructions per wave per tile (8 rows each)
   constexpr int LPW = LK + LV;
-  constexpr int BQ = ATT_WAVES * NQ * 32;        // queries per workgroup
+  constexpr int BQ = NW * NQ * 32;        // queries per workgroup
   static_assert((NST - 2) * LPW < 64, "vmcnt is a 6-bit counter");
   __shared__ __attribute__((aligned(1024))) char lds[NST * STAGE];
 
@@ -106,13 +106,13 @@ __global__ __launch_bounds__(ATT_WAVES * 64, OCC) void attention_bf16_kernel(
   int koff[LK], voff[LV];                                  // element offsets from the tile origin
 #pragma unroll
   for (int i = 0; i < LK; ++i) {
-    const int r = (i * ATT_WAVES + wave) * K_RPI + klr;
+    const int r = (i * NW + wave) * K_RPI + klr;
     const int c = (swz<KROWB>(r, klp) - r * KROWB) >> 4;
     koff[i] = r * DH + c * 8;
   }
 #pragma unroll
   for (int i = 0; i < LV; ++i) {
-    const int r = (i * ATT_WAVES + wave) * 8 + vlr;
+    const int r = (i * NW + wave) * 8 + vlr;
     const int c = (swz<128>(r, vlp) - r * 128) >> 4;
     voff[i] = r * cap + c * 8;                             // row r of the tile is dh index r
   }
@@ -123,10 +123,10 @@ __global__ __launch_bounds__(ATT_WAVES * 64, OCC) void attention_bf16_kernel(
     const bf16_t* vt = Vg + key0;
 #pragma unroll
     for (int i = 0; i < LK; ++i)
-      __builtin_amdgcn_global_load_lds((gptr_t)(kt + koff[i]), (lptr_t)(sk + (i * ATT_WAVES + wave) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(kt + koff[i]), (lptr_t)(sk + (i * NW + wave) * 1024), 16, 0, 0);
 #pragma unroll
     for (int i = 0; i < LV; ++i)
-      __builtin_amdgcn_global_load_lds((gptr_t)(vt + voff[i]), (lptr_t)(sv + (i * ATT_WAVES + wave) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(vt + voff[i]), (lptr_t)(sv + (i * NW + wave) * 1024), 16, 0, 0);
   };
   // The last tile may reach past the valid keys.  Scores of those keys are masked below; the value
   // columns must be exactly zero (0 * garbage could be NaN), so the wave that filled a row zeroes
@@ -136,7 +136,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64, OCC) void attention_bf16_kernel(
     const int first_bad = kv_total - key0;                 // 1..63 here
 #pragma unroll
     for (int i = 0; i < LV; ++i) {
-      const int r = (i * ATT_WAVES + wave) * 8 + vlr;
+      const int r = (i * NW + wave) * 8 + vlr;
       for (int key = first_bad + vlp; key < BKV; key += 8)
         *reinterpret_cast<bf16_t*>(sv + swz<128>(r, key >> 3) + (key & 7) * 2) = (bf16_t)0.0f;
     }
@@ -274,7 +274,12 @@ __global__ __launch_bounds__(ATT_WAVES * 64, OCC) void attention_bf16_kernel(
     if (more) { WAIT_VMCNT((NST - 2) * LPW); } else { WAIT_VMCNT(0); }
     if (t + 2 == ntiles_all && (t + 2) * BKV > kv_total) zero_value_tail(stage + 1 == NST ? 0 : stage + 1, (t + 1) * BKV);
     __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0)
-    __syncthreads();
+    // a bare barrier: __syncthreads() would also wait for the tiles requested for later iterations
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
     stage = stage + 1 == NST ? 0 : stage + 1;
     fill = fill + 1 == NST ? 0 : fill + 1;
   };
@@ -349,11 +354,11 @@ __global__ __launch_bounds__(256) void attention_combine_kernel(const float* __r
   }
 }
 
-template <int DH, int NQ, int NST, int OCC>
+template <int DH, int NQ, int NST, int OCC, int NW>
 hipError_t launch_cfg(const nova_ctx* ctx, hipStream_t st, const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int B,
                       int k, int C, int heads, int cap, int kv_total, float scale_log2, bf16_t* out, float* part_o,
                       float* part_ml) {
-  constexpr int BQ = ATT_WAVES * NQ * 32;
+  constexpr int BQ = NW * NQ * 32;
   const int nqb = (k + BQ - 1) / BQ;
   const int blocks = nqb * heads * B;
   // Key splits: with few, equally long workgroups the last round over the CUs can be mostly
@@ -374,7 +379,7 @@ hipError_t launch_cfg(const nova_ctx* ctx, hipStream_t st, const bf16_t* q, cons
     if (ctx && usable(ctx->attn_split)) nsplit = ctx->attn_split;
   }
   const int64_t rows = (int64_t)B * k;
-  attention_bf16_kernel<DH, NQ, NST, OCC><<<blocks * nsplit, ATT_WAVES * 64, 0, st>>>(
+  attention_bf16_kernel<DH, NQ, NST, OCC, NW><<<blocks * nsplit, NW * 64, 0, st>>>(
       q, kc, vc, k, C, heads, cap, kv_total, nqb, nsplit, rows, scale_log2, out, part_o, part_ml);
   if (nsplit > 1) {
     const int64_t nvec = rows * (C / 4);
@@ -401,15 +406,17 @@ hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void
   // another wave's MFMAs); two groups per wave (half the LDS reads per MFMA, one workgroup per
   // CU) can be forced for tuning.
   int nq = ctx ? ctx->attn_cfg : -1;
-  if (nq < 1 || nq > 2) nq = 1;
-#define ATT_LAUNCH(DH_, NQ_, NST_, OCC_)                                                                       \
-  return launch_cfg<DH_, NQ_, NST_, OCC_>(ctx, st, q, kc, vc, B, k, C, heads, cap, kv_total, scale_log2, out, \
-                                          part_o, part_ml)
+  if (nq < 1 || nq > 3) nq = 1;   // 1: 4 waves x 32 queries (default); 2: 4 waves x 64 queries; 3: 8 waves x 32 queries, deeper ring
+#define ATT_LAUNCH(DH_, NQ_, NST_, OCC_, NW_)                                                                       \
+  return launch_cfg<DH_, NQ_, NST_, OCC_, NW_>(ctx, st, q, kc, vc, B, k, C, heads, cap, kv_total, scale_log2, out, \
+                                               part_o, part_ml)
   if (dh == 64) {
-    if (nq == 1) ATT_LAUNCH(64, 1, 2, 3);
-    ATT_LAUNCH(64, 2, 3, 1);
+    if (nq == 1) ATT_LAUNCH(64, 1, 2, 3, 4);
+    if (nq == 3) ATT_LAUNCH(64, 1, 4, 2, 8);
+    ATT_LAUNCH(64, 2, 3, 1, 4);
   }
-  if (nq == 1) ATT_LAUNCH(128, 1, 2, 2);
-  ATT_LAUNCH(128, 2, 3, 1);
+  if (nq == 1) ATT_LAUNCH(128, 1, 2, 2, 4);
+  if (nq == 3) ATT_LAUNCH(128, 1, 3, 1, 8);
+  ATT_LAUNCH(128, 2, 3, 1, 4);
 #undef ATT_LAUNCH
 }
