@@ -87,26 +87,43 @@ def stage_work(wl, scale, k):
     }
 
 
-def cpu_baseline(hb, wl, scale, k):
-    """Times the CPU oracle, as it stands, on batch row 0 of block 0."""
+def cpu_baseline(hb0, wl, scale, ks):
+    """Times the CPU oracle, as it stands, on three blocks of the step (first, middle, last: the most,
+    a typical and the fewest kept tokens), every batch row, one after the other: roughly 10 s of
+    float64 NumPy on the host cores.  Input generation is not timed."""
     import numpy as np
+    import workloads as WL
     from oracle import nova_oracle as O
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    f64 = lambda t: t[:1].to(dtype=__import__("torch").float64).numpy()
-    t0 = time.perf_counter()
-    H = O.entropy(f64(hb.logits))
-    idx, mask = O.select(H.astype(np.float32), k)
-    W = {n: t.double().numpy() for n, t in hb.weights.items()}
-    y, _, _ = O.pruned_block(f64(hb.x), idx, W, f64(hb.k_prior), f64(hb.v_prior), wl.heads)
-    O.merge_cache(f64(hb.x), y, idx, f64(hb.cache_prev), scale.prev_grid, scale.prev_grid, scale.grid, scale.grid)
-    dt = time.perf_counter() - t0
-    return {"value": k / dt, "unit": "kept tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{wl.name} block 0, batch row 0 of {wl.B} (k={k}): entropy+select+pruned block+merge "
-                      f"in float64 NumPy, {dt:.1f} s"}
+    torch = __import__("torch")
+    blocks = sorted({0, wl.L // 2, wl.L - 1})
+    rows = min(wl.B, 4)
+    dt, kept = 0.0, 0
+    for j in blocks:
+        if j == 0:
+            logits, x, weights, kp, vp, cp = hb0.logits, hb0.x, hb0.weights, hb0.k_prior, hb0.v_prior, hb0.cache_prev
+        else:
+            kp, vp = WL.make_kv_prior(wl, j, scale)
+            logits, x, weights = WL.make_logits(wl, j, scale), WL.make_x(wl, scale), WL.make_weights(wl, j)
+            cp = WL.make_cache_prev(wl, j, scale)
+        W = {n: t.double().numpy() for n, t in weights.items()}
+        k = ks[j]
+        t0 = time.perf_counter()
+        for b in range(rows):
+            f64 = lambda t: t[b:b + 1].to(dtype=torch.float64).numpy()
+            H = O.entropy(f64(logits))
+            idx, mask = O.select(H.astype(np.float32), k)
+            y, _, _ = O.pruned_block(f64(x), idx, W, f64(kp), f64(vp), wl.heads)
+            O.merge_cache(f64(x), y, idx, f64(cp), scale.prev_grid, scale.prev_grid, scale.grid, scale.grid)
+        dt += time.perf_counter() - t0
+        kept += rows * k
+    return {"value": kept / dt, "unit": "kept tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{wl.name} blocks {blocks}, batch rows 0..{rows - 1} of {wl.B} ({kept} kept tokens): "
+                      f"entropy+select+pruned block+merge in float64 NumPy, {dt:.1f} s"}
 
 
 def image_chain(nova, wl, weights, gen):
@@ -344,7 +361,7 @@ def main():
     if args.image:
         out["image_chain"] = image_chain(nova, wl, [st.weights for st in runner.blocks], gen)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(hb0, wl, scale, ks[0])
+        out["cpu_baseline"] = cpu_baseline(hb0, wl, scale, ks)
     print(json.dumps(out))
 
 
