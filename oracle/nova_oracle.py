@@ -9,6 +9,9 @@ What each function follows:
   entropy, mean_entropy   -- token predictive entropy (Sec. 3.3, "Adaptive
                              Acceleration Activation", the entropy equation and
                              the scale-mean equation); natural logarithm.
+  head_entropy            -- the same entropy taken straight from a linear head's input
+                             (Sec. 4, "Entropy Computation Overhead": the distributions are
+                             the ones decoding produces anyway).
   select                  -- "pruning low-entropy tokens according to the token
                              reduction ratio" (Sec. 3.3, Dual-Linkage Acceleration,
                              last sentence) / "maintaining highest-entropy tokens"
@@ -54,6 +57,16 @@ def entropy(logits: np.ndarray) -> np.ndarray:
     with np.errstate(divide="ignore", invalid="ignore"):
         plogp = np.where(p > 0.0, p * np.log(p), 0.0)
     return -np.sum(plogp, axis=-1)
+
+
+def head_entropy(hidden: np.ndarray, w_head: np.ndarray, b_head=None) -> np.ndarray:
+    """Entropy of the distributions a linear prediction head produces: logits = hidden W^T + b
+    (W out-feature major, [V, C]), then `entropy` over V.  The paper takes the distributions
+    from standard decoding (Sec. 4, "Entropy Computation Overhead"); this is that composition."""
+    logits = _f64(hidden) @ _f64(w_head).T
+    if b_head is not None:
+        logits = logits + _f64(b_head)
+    return entropy(logits)
 
 
 def mean_entropy(H: np.ndarray) -> np.ndarray:

@@ -174,3 +174,36 @@ def test_select_invariants_large():
         tied_pruned = np.flatnonzero((H[b] == thr) & (mask[b] == 0))
         if len(tied_kept) and len(tied_pruned):
             assert tied_kept.max() < tied_pruned.min()
+
+
+# ---------------------------------------------------------------------------------------------
+# entropy straight from a linear head (Sec. 4, "Entropy Computation Overhead")
+# ---------------------------------------------------------------------------------------------
+def test_head_entropy_special_cases():
+    rng = np.random.default_rng(5)
+    V, C = 37, 11
+    W = rng.standard_normal((V, C))
+    # zero hidden state: all logits equal the bias; without a bias the distribution is uniform
+    assert np.allclose(O.head_entropy(np.zeros((3, C)), W), np.log(V), rtol=1e-14)
+    b = rng.standard_normal(V)
+    assert np.allclose(O.head_entropy(np.zeros((2, C)), W, b), O.entropy(b[None, :].repeat(2, 0)), rtol=1e-14)
+    # a one-hot hidden state selects one column of W as the logits
+    for c in (0, 4, 10):
+        h = np.zeros((1, C)); h[0, c] = 1.0
+        assert np.allclose(O.head_entropy(h, W), O.entropy(W[:, c][None, :]), rtol=1e-14)
+    # adding a constant to every logit (a bias shift) changes nothing
+    h = rng.standard_normal((5, C))
+    assert np.allclose(O.head_entropy(h, W, b), O.head_entropy(h, W, b + 3.25), rtol=1e-12)
+
+
+def test_head_entropy_against_scalar_loops():
+    rng = np.random.default_rng(6)
+    M, V, C = 4, 9, 5
+    h, W, b = rng.standard_normal((M, C)), rng.standard_normal((V, C)), rng.standard_normal(V)
+    got = O.head_entropy(h, W, b)
+    for m in range(M):
+        logits = [sum(h[m, c] * W[v, c] for c in range(C)) + b[v] for v in range(V)]
+        mx = max(logits)
+        Z = sum(math.exp(x - mx) for x in logits)
+        H = -sum((math.exp(x - mx) / Z) * ((x - mx) - math.log(Z)) for x in logits)
+        assert got[m] == pytest.approx(H, rel=1e-12)
