@@ -101,6 +101,25 @@ int nova_entropy(nova_ctx* ctx, void* stream, const void* logits, int logits_dty
                  float* entropy, float* mean_entropy);
 
 /*
+ * Token entropy straight from a linear prediction head (Sec. 4, "Entropy Computation
+ * Overhead": the distributions are the ones decoding produces; entropy equation of Sec. 3.3):
+ *   logits = hidden W_head^T + b_head   (fp32 accumulation on the matrix cores, never stored)
+ *   entropy[token] = -sum_v p(v) ln p(v),  p = softmax(logits[token, :])
+ * i.e. nova_entropy of the head's output without the [tokens, V] logits round trip through HBM.
+ *   hidden        [batch*rows_per_batch, C]  NOVA_BF16 (the only dtype supported), C % 64 == 0
+ *   w_head        [V, C] out-feature major;  b_head [V] or NULL
+ *   entropy       out [batch*rows_per_batch] fp32;  mean_entropy out [batch] fp32 or NULL
+ *   workspace     device scratch of at least nova_head_entropy_workspace_bytes(...), 16-byte aligned
+ * Inputs must be finite.  The logits differ from bf16-stored ones by that rounding, so the result
+ * agrees with nova_entropy on stored logits only to the storage precision; against exact
+ * arithmetic on the same inputs |dH| <= 1e-4 |H| + 1e-5.
+ */
+size_t nova_head_entropy_workspace_bytes(int64_t rows_per_batch, int batch, int V);
+int nova_head_entropy(nova_ctx* ctx, void* stream, const void* hidden, const void* w_head,
+                      const void* b_head, int dtype, int64_t rows_per_batch, int batch, int C, int V,
+                      float* entropy, float* mean_entropy, void* workspace, size_t workspace_bytes);
+
+/*
  * Entropy-guided token selection (Sec. 3.3, "Dual-Linkage Acceleration", final
  * sentence: the lowest-entropy tokens are pruned at the reduction ratio; Sec. 3.2:
  * the highest-entropy tokens are maintained).  For each batch row the k tokens

@@ -77,6 +77,10 @@ def load_library() -> C.CDLL:
     lib.nova_workspace_bytes.restype = C.c_size_t
     lib.nova_entropy.argtypes = [vp, vp, vp, i32, i64, i32, i32, i64, vp, vp]
     lib.nova_select.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp]
+    lib.nova_head_entropy_workspace_bytes.argtypes = [i64, i32, i32]
+    lib.nova_head_entropy_workspace_bytes.restype = C.c_size_t
+    lib.nova_head_entropy.argtypes = [vp, vp, vp, vp, vp, i32, i64, i32, i32, i32, vp, vp, vp, C.c_size_t]
+    lib.nova_head_entropy.restype = i32
     lib.nova_pruned_block.argtypes = [vp, vp, C.POINTER(_Shape), C.POINTER(_Weights), vp, vp, vp, vp, vp, vp,
                                       C.c_size_t]
     lib.nova_merge_cache.argtypes = [vp, vp, i32] + [i32] * 7 + [vp] * 7
@@ -192,6 +196,20 @@ class Nova:
         rc = self.lib.nova_entropy(self.ctx, _stream(), _ptr(logits), _dtype_code(logits), N, B, V,
                                    logits.stride(1), _ptr(entropy), _ptr(mean))
         self._check(rc, "nova_entropy")
+
+    # -- nova_head_entropy ----------------------------------------------------------
+    def head_entropy_workspace_bytes(self, rows_per_batch: int, batch: int, V: int) -> int:
+        return int(self.lib.nova_head_entropy_workspace_bytes(rows_per_batch, batch, V))
+
+    def head_entropy(self, hidden: torch.Tensor, w_head: torch.Tensor, b_head: Optional[torch.Tensor],
+                     entropy: torch.Tensor, workspace: torch.Tensor, mean: Optional[torch.Tensor] = None):
+        """hidden [B, N, C] bf16, w_head [V, C], b_head [V] or None -> entropy [B, N] f32 (and mean [B])."""
+        B, N, Cc = hidden.shape
+        V = w_head.shape[0]
+        rc = self.lib.nova_head_entropy(self.ctx, _stream(), _ptr(hidden), _ptr(w_head), _ptr(b_head),
+                                        _dtype_code(hidden), N, B, Cc, V, _ptr(entropy), _ptr(mean),
+                                        _ptr(workspace), workspace.numel() * workspace.element_size())
+        self._check(rc, "nova_head_entropy")
 
     # -- nova_select ----------------------------------------------------------------
     def select(self, entropy: torch.Tensor, k: int, kept_idx: torch.Tensor, keep_mask: torch.Tensor,

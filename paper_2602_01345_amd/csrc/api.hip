@@ -157,6 +157,30 @@ int nova_entropy(nova_ctx* ctx, void* stream, const void* logits, int logits_dty
   return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
 }
 
+size_t nova_head_entropy_workspace_bytes(int64_t rows_per_batch, int batch, int V) {
+  if (rows_per_batch <= 0 || batch <= 0 || V < 1 || rows_per_batch * batch > ((int64_t)1 << 24)) return 0;
+  return head_entropy_workspace_bytes((int)(rows_per_batch * batch), V);
+}
+
+int nova_head_entropy(nova_ctx* ctx, void* stream, const void* hidden, const void* w_head, const void* b_head,
+                      int dtype, int64_t rows_per_batch, int batch, int C, int V, float* entropy,
+                      float* mean_entropy, void* workspace, size_t workspace_bytes) {
+  if (!ctx) return NOVA_ERR_INVALID_ARG;
+  if (dtype != NOVA_BF16) return NOVA_ERR_UNSUPPORTED;
+  if (rows_per_batch < 0 || batch < 0 || V < 1 || C < 1) return NOVA_ERR_INVALID_ARG;
+  if (rows_per_batch == 0 || batch == 0) return NOVA_OK;
+  if (rows_per_batch * batch > ((int64_t)1 << 24)) return NOVA_ERR_UNSUPPORTED;
+  if (C % 64 != 0) return NOVA_ERR_UNSUPPORTED;
+  if (!hidden || !w_head || !entropy || !workspace) return NOVA_ERR_INVALID_ARG;
+  for (const void* p : {hidden, w_head, b_head, (const void*)workspace})
+    if (reinterpret_cast<uintptr_t>(p) % 16 != 0) return NOVA_ERR_INVALID_ARG;
+  if (workspace_bytes < nova_head_entropy_workspace_bytes(rows_per_batch, batch, V)) return NOVA_ERR_WORKSPACE;
+  if (int rc = set_device(ctx)) return rc;
+  hipError_t e = launch_head_entropy(ctx, static_cast<hipStream_t>(stream), hidden, w_head, b_head,
+                                     (int)rows_per_batch, batch, C, V, entropy, mean_entropy, workspace);
+  return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
+}
+
 int nova_select(nova_ctx* ctx, void* stream, const float* entropy, int B, int N, int k, const int32_t* k_per_row,
                 int32_t* kept_idx, uint8_t* keep_mask) {
   if (!ctx) return NOVA_ERR_INVALID_ARG;

@@ -8,7 +8,8 @@ enum EpiMode {
   EPI_QKV = 0,        // + b_qkv; split into q (workspace), key rows and value columns of the caches
   EPI_ATTN_OUT = 1,   // x1 = x[gathered row] + acc + b_o
   EPI_GELU = 2,       // hid = GELU(acc + b_fc1), erf form
-  EPI_RESIDUAL = 3    // y = x1 + acc + b_fc2
+  EPI_RESIDUAL = 3,   // y = x1 + acc + b_fc2
+  EPI_ENTROPY = 4     // acc + b are logits: only per-row softmax-entropy partials of the tile's columns leave the kernel
 };
 
 template <typename T>
@@ -24,6 +25,8 @@ struct EpiParams {
   const T* res;         // EPI_ATTN_OUT: x [B, Ntok, C] gathered through idx; EPI_RESIDUAL: x1 [M, C]
   const int32_t* idx;   // [B, k]
   int Ntok;
+  // EPI_ENTROPY: [column tiles][M] partials (m, S, T, unused) with S = sum e^(x-m), T = sum (m-x) e^(x-m)
+  f32x4* ent_part;
 };
 
 // Exact-form GELU 0.5 v (1 + erf(v / sqrt 2)).  erf through the rational approximation 7.1.26 of
@@ -41,6 +44,21 @@ __device__ __forceinline__ float gelu_erf(float v) {
   const float e = __builtin_amdgcn_exp2f(-x * x * 1.4426950408889634f);
   const float erf_abs = fmaf(-poly, e, 1.0f);               // erf(|v| / sqrt 2)
   return 0.5f * v * (1.0f + copysignf(erf_abs, v));
+}
+
+// Entropy partials of two disjoint column sets of one row, merged in place into the first:
+// against the common maximum M, S = sum f_i S_i and T = sum f_i (T_i + (M - m_i) S_i), f_i = e^(m_i - M).
+// An empty set is m = -inf, S = T = 0.
+__device__ __forceinline__ void entropy_merge(float& m, float& S, float& T, float m2, float S2, float T2) {
+  const float M = fmaxf(m, m2);
+  if (M == -INFINITY) return;
+  const float kLog2e = 1.4426950408889634f;
+  const float f1 = __builtin_amdgcn_exp2f((m - M) * kLog2e), f2 = __builtin_amdgcn_exp2f((m2 - M) * kLog2e);
+  const float t1 = (m == -INFINITY) ? 0.0f : f1 * fmaf(M - m, S, T);
+  const float t2 = (m2 == -INFINITY) ? 0.0f : f2 * fmaf(M - m2, S2, T2);
+  S = f1 * S + f2 * S2;
+  T = t1 + t2;
+  m = M;
 }
 
 template <typename T, int MODE>

@@ -200,6 +200,58 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
     stage = next;
     fill = fill + 1 == NST ? 0 : fill + 1;
   }
+  if constexpr (MODE == EPI_ENTROPY) {
+    // The accumulators (+ bias) are logits that never leave the chip: each lane reduces the columns
+    // it holds of a token row to (max, S, T), the two half-waves and then the waves that share the
+    // row merge their partials, and one (m, S, T) per row and column tile goes to memory.
+    constexpr float kLog2e = 1.4426950408889634f;
+    f32x4* lp = reinterpret_cast<f32x4*>(lds);           // [WN][BM]; the stage ring is free after the last barrier
+    float bias[TN][16];
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int col = n0 + wn * (BN / WN) + jn * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        bias[jn][r] = col >= Nout ? -INFINITY : (ep.bias ? (float)ep.bias[col] : 0.0f);   // -inf masks the edge
+      }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      float m = -INFINITY;
+#pragma unroll
+      for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          acc[i][jn][r] += bias[jn][r];
+          m = fmaxf(m, acc[i][jn][r]);
+        }
+      float S = 0.0f, T = 0.0f;
+      if (m != -INFINITY) {
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float d = fmaxf(acc[i][jn][r] - m, -200.0f);     // e^-200 == 0: masked columns add nothing
+            const float e = __builtin_amdgcn_exp2f(d * kLog2e);
+            S += e;
+            T = fmaf(-d, e, T);
+          }
+      }
+      entropy_merge(m, S, T, __shfl_xor(m, 32, 64), __shfl_xor(S, 32, 64), __shfl_xor(T, 32, 64));
+      if (half == 0) lp[wn * BM + wm * (BM / WM) + i * 32 + r32] = f32x4{m, S, T, 0.0f};
+    }
+    __syncthreads();
+    for (int row = tid; row < BM; row += NW * 64) {
+      const f32x4 a = lp[row];
+      float pm = a[0], pS = a[1], pT = a[2];
+#pragma unroll
+      for (int w = 1; w < WN; ++w) {
+        const f32x4 b2 = lp[w * BM + row];
+        entropy_merge(pm, pS, pT, b2[0], b2[1], b2[2]);
+      }
+      if (m0 + row < M) ep.ent_part[(int64_t)tn * M + m0 + row] = f32x4{pm, pS, pT, 0.0f};
+    }
+    return;
+  }
   // ---- epilogue, stage 1: accumulators (+ bias, GELU) -> bf16 tile in LDS, row-major --------
   // The MFMAs ran with the weight rows as the A operand, so a lane owns token l % 32 of each MFMA
   // tile and, per register group r / 4, four consecutive output features: one 8-byte LDS write.
@@ -364,6 +416,16 @@ hipError_t launch_mode(const nova_ctx* ctx, hipStream_t st, const bf16_t* A, con
 
 }  // namespace
 
+// Output columns per tile of the configuration launch_gemm_bf16 uses for this shape.
+int gemm_bf16_tile_cols(const nova_ctx* ctx, int M, int Nout, int K) {
+  switch (pick_cfg(ctx, M, Nout, K)) {
+    case 0: case 5: return 128;
+    case 1: case 6: return 256;
+    case 3: case 4: return 32;
+    default: return 128;
+  }
+}
+
 hipError_t launch_gemm_bf16(const nova_ctx* ctx, hipStream_t st, int mode, const void* A, const void* W, int M,
                             int Nout, int K, const EpiParams<bf16_t>& ep) {
   const bf16_t* a = static_cast<const bf16_t*>(A);
@@ -372,6 +434,7 @@ hipError_t launch_gemm_bf16(const nova_ctx* ctx, hipStream_t st, int mode, const
     case EPI_QKV: return launch_mode<EPI_QKV>(ctx, st, a, w, M, Nout, K, ep);
     case EPI_ATTN_OUT: return launch_mode<EPI_ATTN_OUT>(ctx, st, a, w, M, Nout, K, ep);
     case EPI_GELU: return launch_mode<EPI_GELU>(ctx, st, a, w, M, Nout, K, ep);
+    case EPI_ENTROPY: return launch_mode<EPI_ENTROPY>(ctx, st, a, w, M, Nout, K, ep);
     default: return launch_mode<EPI_RESIDUAL>(ctx, st, a, w, M, Nout, K, ep);
   }
 }

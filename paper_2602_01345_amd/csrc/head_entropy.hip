@@ -1,0 +1,57 @@
+// Token entropy straight from a linear prediction head (Sec. 4, "Entropy Computation Overhead":
+// the entropy is taken from the distributions decoding produces anyway; Sec. 3.3, "Adaptive
+// Acceleration Activation": the entropy equation).  logits = hidden W^T + b are formed tile by tile
+// on the matrix cores and reduced on the spot, so the [tokens, V] logits never reach HBM: the GEMM's
+// entropy epilogue leaves one (max, S, T) partial per row and column tile, and the kernel here
+// merges a row's partials: H = ln S + T / S with S = sum e^(x-m), T = sum (m-x) e^(x-m).
+#include "common.h"
+#include "epilogue.h"
+#include "nova_internal.h"
+
+namespace {
+
+__global__ __launch_bounds__(256) void head_entropy_combine_kernel(const f32x4* __restrict__ part, int tiles_n,
+                                                                   int M, float* __restrict__ H,
+                                                                   float* __restrict__ mean, int rows_per_batch,
+                                                                   float inv_rows) {
+  const int row = blockIdx.x * blockDim.x + threadIdx.x;
+  if (row >= M) return;
+  const f32x4 a = part[row];
+  float m = a[0], S = a[1], T = a[2];
+  for (int t = 1; t < tiles_n; ++t) {
+    const f32x4 b = part[(int64_t)t * M + row];
+    entropy_merge(m, S, T, b[0], b[1], b[2]);
+  }
+  float h = logf(S) + T / S;
+  h = h < 0.0f ? 0.0f : h;
+  H[row] = h;
+  if (mean) atomicAdd(mean + row / rows_per_batch, h * inv_rows);
+}
+
+__global__ void zero_kernel(float* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0.0f;
+}
+
+}  // namespace
+
+size_t head_entropy_workspace_bytes(int M, int V) {
+  // one 16-byte partial per row and column tile; the narrowest tile configuration has 32 columns
+  return (size_t)((V + 31) / 32) * (size_t)M * sizeof(f32x4);
+}
+
+hipError_t launch_head_entropy(const nova_ctx* ctx, hipStream_t st, const void* hidden, const void* w_head,
+                               const void* b_head, int rows_per_batch, int batch, int C, int V, float* H,
+                               float* mean, void* workspace) {
+  const int M = rows_per_batch * batch;
+  EpiParams<bf16_t> ep{};
+  ep.bias = static_cast<const bf16_t*>(b_head);
+  ep.ent_part = static_cast<f32x4*>(workspace);
+  hipError_t e = launch_gemm_bf16(ctx, st, EPI_ENTROPY, hidden, w_head, M, V, C, ep);
+  if (e != hipSuccess) return e;
+  const int bn = gemm_bf16_tile_cols(ctx, M, V, C);
+  if (mean) zero_kernel<<<(batch + 255) / 256, 256, 0, st>>>(mean, batch);
+  head_entropy_combine_kernel<<<(M + 255) / 256, 256, 0, st>>>(ep.ent_part, (V + bn - 1) / bn, M, H, mean,
+                                                               rows_per_batch, 1.0f / (float)rows_per_batch);
+  return hipGetLastError();
+}

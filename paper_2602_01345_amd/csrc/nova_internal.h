@@ -85,6 +85,11 @@ hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shap
 template <typename T> struct EpiParams;
 hipError_t launch_gemm_bf16(const nova_ctx* ctx, hipStream_t st, int mode, const void* A, const void* W, int M,
                             int Nout, int K, const EpiParams<__bf16>& ep);
+int gemm_bf16_tile_cols(const nova_ctx* ctx, int M, int Nout, int K);
+size_t head_entropy_workspace_bytes(int M, int V);
+hipError_t launch_head_entropy(const nova_ctx* ctx, hipStream_t st, const void* hidden, const void* w_head,
+                               const void* b_head, int rows_per_batch, int batch, int C, int V, float* H,
+                               float* mean, void* workspace);
 // attention_bf16.hip: attn[B*k, C] = softmax(q K^T / sqrt(dh)) V per head over kv_total cached keys
 // part_o / part_ml: workspace for split-key partial results ([max_split, B*k, C] and [max_split, B*k, heads, 2]
 // fp32), or nullptr to forbid splitting
