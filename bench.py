@@ -356,6 +356,30 @@ def main():
                                "bound": "mfma", "logits_bytes_not_written": wl.B * scale.N * wl.V * 2}
         del hh, hw, hH, hws
 
+    # what the chip sustains for plain kernels (published peaks: HBM 8 TB/s, dense bf16 MFMA 2.5 PFLOP/s)
+    peaks = {}
+    if not args.no_stage_pass:
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            work = 0.0
+            for _ in range(reps):
+                work += fn()
+            b.record()
+            torch.cuda.synchronize()
+            return work / (a.elapsed_time(b) * 1e-3)
+        sink = torch.zeros(1, device="cuda")
+        big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")      # 1 GiB: four times the infinity cache
+        big.fill_(1)
+        big2 = torch.empty_like(big)
+        peaks["hbm_read_GBs"] = round(timed(lambda: nova.probe(0, big, None, 1, sink), 5) / 1e9, 1)
+        peaks["hbm_copy_GBs"] = round(timed(lambda: nova.probe(1, big, big2, 1, sink), 5) / 1e9, 1)
+        peaks["mfma_bf16_TFLOPs"] = round(timed(lambda: nova.probe(2, None, None, 2000, sink), 3) / 1e12, 1)
+        peaks["note"] = "plain kernels of this library (nova_probe): 1 GiB streaming read, 1 GiB copy (read+write bytes), MFMA-only loop"
+        del big, big2
+
     traffic = None
     tf = os.path.join(ROOT, "profiles", f"attention_{args.config}_hbm_traffic.txt")
     if os.path.exists(tf):
@@ -377,6 +401,7 @@ def main():
                      "avg_launch_us": dom_avg_s * 1e6, "flops_per_launch": dom_flops},
         "kernels": kernels,
         "hbm_kernels_sustained": hbm,
+        "achievable_peaks": peaks,
     }
     if args.image:
         out["image_chain"] = image_chain(nova, wl, [st.weights for st in runner.blocks], gen)

@@ -242,6 +242,21 @@ enum {
 int nova_profile_stages(nova_ctx* ctx, uint32_t stage_mask);
 int nova_profile_collect(nova_ctx* ctx, int stage, double* total_ms, int64_t* launches);
 
+/*
+ * Instrumentation (not part of the hot path): launches one plain kernel that shows what the
+ * device sustains, for reading roofline fractions against an achievable figure.  The caller
+ * times the launch with events on `stream`; *work (host) receives the bytes moved or the flops
+ * done by the launch.
+ *   NOVA_PROBE_READ   streams `bytes` from src (16 bytes per lane, grid-stride)
+ *   NOVA_PROBE_COPY   copies `bytes` from src to dst (work = 2 * bytes)
+ *   NOVA_PROBE_MFMA   8 waves per CU, `iters` rounds of 32 independent bf16 32x32x16 MFMAs each
+ * src / dst: device, 16-byte aligned; sink: device fp32 [1] (never written in practice).
+ */
+enum { NOVA_PROBE_READ = 0, NOVA_PROBE_COPY = 1, NOVA_PROBE_MFMA = 2 };
+int nova_probe(nova_ctx* ctx, void* stream, int kind, const void* src, void* dst, int64_t bytes,
+               int iters, float* sink, double* work);
+
+
 #ifdef __cplusplus
 }
 #endif

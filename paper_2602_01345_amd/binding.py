@@ -89,6 +89,8 @@ def load_library() -> C.CDLL:
     lib.nova_activation_scale.argtypes = [C.POINTER(C.c_double), i32, i32, C.c_double, C.POINTER(i32)]
     lib.nova_scale_ratio.argtypes = [i32, i32, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_double)]
     lib.nova_layer_ratio.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp]
+    lib.nova_probe.argtypes = [vp, vp, i32, vp, vp, i64, i32, vp, C.POINTER(C.c_double)]
+    lib.nova_probe.restype = i32
     lib.nova_profile_stages.restype = i32
     lib.nova_profile_collect.restype = i32
     for f in (lib.nova_create, lib.nova_destroy, lib.nova_entropy, lib.nova_select, lib.nova_pruned_block,
@@ -177,6 +179,16 @@ class Nova:
         self._check(self.lib.nova_profile_collect(self.ctx, int(stage), C.byref(ms), C.byref(n)),
                     "nova_profile_collect")
         return ms.value, n.value
+
+    def probe(self, kind: int, src: Optional[torch.Tensor], dst: Optional[torch.Tensor], iters: int,
+              sink: torch.Tensor) -> float:
+        """nova_probe: launches one achievable-peak kernel; returns the bytes moved / flops done."""
+        work = C.c_double(0.0)
+        nbytes = 0 if src is None else src.numel() * src.element_size()
+        rc = self.lib.nova_probe(self.ctx, _stream(), int(kind), _ptr(src), _ptr(dst), nbytes, int(iters),
+                                 _ptr(sink), C.byref(work))
+        self._check(rc, "nova_probe")
+        return work.value
 
     # -- nova_layer_ratio -----------------------------------------------------------
     def layer_ratio(self, mean_entropy: torch.Tensor, entropy_sum: torch.Tensor, ratio_t: torch.Tensor, j: int,

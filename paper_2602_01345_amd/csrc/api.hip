@@ -98,6 +98,35 @@ int nova_destroy(nova_ctx* ctx) {
   return NOVA_OK;
 }
 
+int nova_probe(nova_ctx* ctx, void* stream, int kind, const void* src, void* dst, int64_t bytes, int iters,
+               float* sink, double* work) {
+  if (!ctx || !sink || !work) return NOVA_ERR_INVALID_ARG;
+  if (int rc = set_device(ctx)) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e = hipSuccess;
+  switch (kind) {
+    case NOVA_PROBE_READ:
+      if (!src || bytes < 16 || reinterpret_cast<uintptr_t>(src) % 16) return NOVA_ERR_INVALID_ARG;
+      e = launch_probe_read(st, ctx->num_cus, src, bytes, sink);
+      *work = (double)(bytes / 16 * 16);
+      break;
+    case NOVA_PROBE_COPY:
+      if (!src || !dst || bytes < 16 || reinterpret_cast<uintptr_t>(src) % 16 || reinterpret_cast<uintptr_t>(dst) % 16)
+        return NOVA_ERR_INVALID_ARG;
+      e = launch_probe_copy(st, ctx->num_cus, src, dst, bytes);
+      *work = 2.0 * (double)(bytes / 16 * 16);
+      break;
+    case NOVA_PROBE_MFMA:
+      if (iters < 1) return NOVA_ERR_INVALID_ARG;
+      e = launch_probe_mfma(st, ctx->num_cus, iters, sink);
+      // workgroups x waves x rounds x MFMAs x flops of one 32x32x16 MFMA
+      *work = (double)ctx->num_cus * 8.0 * (double)iters * 32.0 * (2.0 * 32 * 32 * 16);
+      break;
+    default: return NOVA_ERR_INVALID_ARG;
+  }
+  return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
+}
+
 int nova_profile_stages(nova_ctx* ctx, uint32_t stage_mask) {
   if (!ctx || (stage_mask >> NOVA_STAGE_COUNT) != 0) return NOVA_ERR_INVALID_ARG;
   ctx->prof_mask = stage_mask;

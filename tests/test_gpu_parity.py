@@ -257,3 +257,17 @@ def test_argument_errors(hx):
     assert n.workspace_bytes(ok) > 0
     assert n.workspace_bytes(BlockShape(1, 2, 16, 128, 2, 62, 64, 4)) == 0     # P + k > capacity
     assert n.workspace_bytes(BlockShape(1, 2, 16, 96, 2, 0, 64, 4)) == 0       # dh = 48 unsupported in bf16
+
+
+def test_probe_kernels_report_their_work(hx):
+    """The achievable-peak probes (instrumentation) run and report bytes / flops; the copy copies."""
+    nova = hx.nova()
+    sink = torch.zeros(1, device="cuda")
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    assert nova.probe(0, src, None, 1, sink) == src.numel() * 4
+    assert nova.probe(1, src, dst, 1, sink) == 2 * src.numel() * 4
+    flops = nova.probe(2, None, None, 3, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst) and float(sink) == 0.0
+    assert flops == torch.cuda.get_device_properties(0).multi_processor_count * 8 * 3 * 32 * 2 * 32 * 32 * 16
