@@ -54,3 +54,13 @@ def test_workload_keep_tables():
     assert [s.kv_len for s in WL.WORKLOADS["cfg5"].scales] == [1497, 2521, 4121, 6425]
     assert WL.WORKLOADS["cfg4"].last.kv_len == 1216 and WL.WORKLOADS["cfg1"].last.kv_len == 424
     assert WL.WORKLOADS["cfg3"].scales[0].kv_len == 255
+
+
+def test_grid_lists_match_the_workloads():
+    import workloads as WL
+    for name, wl in WL.WORKLOADS.items():
+        grids = WL.grid_list(wl)
+        for s in wl.scales:
+            t = grids.index(s.grid)
+            assert s.kv_len == sum(g * g for g in grids[:t]), name
+            assert s.prev_grid == grids[t - 1], name

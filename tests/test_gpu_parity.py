@@ -271,3 +271,44 @@ def test_probe_kernels_report_their_work(hx):
     torch.cuda.synchronize()
     assert torch.equal(src, dst) and float(sink) == 0.0
     assert flops == torch.cuda.get_device_properties(0).multi_processor_count * 8 * 3 * 32 * 2 * 32 * 32 * 16
+
+
+@pytest.mark.parametrize("P,k", [(0, 1), (0, 40), (3, 61), (64, 64), (127, 1), (500, 289)])
+def test_block_bf16_key_range_edges(hx, P, k):
+    """No prior keys at all, one partial key tile, exact tile multiples, a one-key ragged tail."""
+    _say(f"block bf16 P={P} k={k}")
+    wl = _custom("bf16", B=2, grid=17, prev=13, P=P, C=128, heads=2)
+    hb = hx.make_host_block(wl, 0, k=k)
+    errs = hx.check_block(hb, hx.BF16_TOL)
+    _say(f"   errors {errs}")
+
+
+@pytest.mark.parametrize("split", [2, 3, 4])
+def test_block_bf16_forced_key_splits(hx, split, monkeypatch):
+    """The split-key attention path (partial sums merged by the combine kernel) with every split count."""
+    from paper_2602_01345_amd import Nova
+    monkeypatch.setenv("NOVA_ATTN_SPLIT", str(split))
+    forced = Nova(0)                                   # the knob is read when a context is created
+    monkeypatch.setattr(hx, "_NOVA", forced)
+    wl = _custom("bf16", B=1, grid=20, prev=16, P=700, C=256, heads=2)      # 1100 keys = 18 tiles, dh = 128
+    hb = hx.make_host_block(wl, 0, k=400)
+    errs = hx.check_block(hb, hx.BF16_TOL)
+    _say(f"   split {split}: errors {errs}")
+    wl = _custom("bf16", B=2, grid=12, prev=8, P=260, C=128, heads=2)       # dh = 64, ragged last tile
+    hb = hx.make_host_block(wl, 0, k=77)
+    hx.check_block(hb, hx.BF16_TOL)
+
+
+def test_block_is_deterministic(hx):
+    """Two runs on the same inputs give the same bits (no atomics on the block / merge path)."""
+    wl = _custom("bf16", B=2, grid=24, prev=18, P=900, C=256, heads=4)
+    hb = hx.make_host_block(wl, 0, k=300)
+    outs = []
+    for _ in range(2):
+        runner, st, x = hx.to_gpu(hb)
+        runner.run_block(st, x)
+        torch.cuda.synchronize()
+        outs.append([t.clone() for t in (st.entropy, st.kept_idx, st.keep_mask, st.y_kept, st.out, st.cache_new,
+                                         st.k_cache, st.v_cache)])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
