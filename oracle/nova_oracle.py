@@ -12,6 +12,10 @@ What each function follows:
   head_entropy            -- the same entropy taken straight from a linear head's input
                              (Sec. 4, "Entropy Computation Overhead": the distributions are
                              the ones decoding produces anyway).
+  bitwise_entropy         -- the entropy equation for a head that predicts a token as d
+                             independent bits (the Infinity backbone of Sec. 4): the sum of
+                             the bits' binary entropies.  This factorised form is this
+                             build's reading; the paper prints only the categorical one.
   select                  -- "pruning low-entropy tokens according to the token
                              reduction ratio" (Sec. 3.3, Dual-Linkage Acceleration,
                              last sentence) / "maintaining highest-entropy tokens"
@@ -67,6 +71,15 @@ def head_entropy(hidden: np.ndarray, w_head: np.ndarray, b_head=None) -> np.ndar
     if b_head is not None:
         logits = logits + _f64(b_head)
     return entropy(logits)
+
+
+def bitwise_entropy(bit_logits: np.ndarray) -> np.ndarray:
+    """Token entropy of a bitwise token head: the token is d independent binary choices, bit i with
+    the two logits bit_logits[..., i, 0:2], so the token's entropy is the sum of the d binary
+    entropies (the entropy equation of Sec. 3.3 applied to a product distribution).  [..., d, 2] -> [...]."""
+    x = np.asarray(bit_logits, dtype=np.float64)
+    assert x.shape[-1] == 2
+    return np.sum(entropy(x), axis=-1)
 
 
 def mean_entropy(H: np.ndarray) -> np.ndarray:

@@ -207,3 +207,37 @@ def test_head_entropy_against_scalar_loops():
         Z = sum(math.exp(x - mx) for x in logits)
         H = -sum((math.exp(x - mx) / Z) * ((x - mx) - math.log(Z)) for x in logits)
         assert got[m] == pytest.approx(H, rel=1e-12)
+
+
+# ---------------------------------------------------------------------------------------------
+# bitwise token heads: a token is d independent binary choices
+# ---------------------------------------------------------------------------------------------
+def test_bitwise_entropy_closed_forms():
+    # all bits undecided: d ln 2; all bits certain: 0
+    assert np.allclose(O.bitwise_entropy(np.zeros((3, 16, 2))), 16 * math.log(2.0), rtol=1e-15)
+    sure = np.zeros((1, 8, 2)); sure[..., 1] = 80.0
+    assert O.bitwise_entropy(sure)[0] < 1e-30
+    # binary entropy of p = 1/4 on every bit: logit difference ln 3
+    x = np.zeros((2, 5, 2)); x[..., 0] = math.log(3.0)
+    h = -(0.25 * math.log(0.25) + 0.75 * math.log(0.75))
+    assert np.allclose(O.bitwise_entropy(x), 5 * h, rtol=1e-14)
+
+
+def test_bitwise_entropy_is_the_entropy_of_the_product_distribution():
+    # brute force: enumerate all 2^d tokens of the product distribution and apply the categorical equation
+    rng = np.random.default_rng(11)
+    d = 6
+    x = rng.standard_normal((4, d, 2)) * 2.0
+    got = O.bitwise_entropy(x)
+    for r in range(4):
+        p1 = 1.0 / (1.0 + np.exp(x[r, :, 0] - x[r, :, 1]))        # P(bit = 1)
+        H = 0.0
+        for token in range(1 << d):
+            p = 1.0
+            for i in range(d):
+                p *= p1[i] if (token >> i) & 1 else 1.0 - p1[i]
+            H -= p * math.log(p)
+        assert got[r] == pytest.approx(H, rel=1e-12)
+    # shifting both logits of a bit changes nothing; swapping them changes nothing either
+    y = x.copy(); y[:, 2, :] += 1.75; y[:, 4, :] = y[:, 4, ::-1]
+    assert np.allclose(O.bitwise_entropy(y), got, rtol=1e-13)
