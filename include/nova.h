@@ -101,6 +101,18 @@ int nova_entropy(nova_ctx* ctx, void* stream, const void* logits, int logits_dty
                  float* entropy, float* mean_entropy);
 
 /*
+ * Token entropy of a bitwise token head (a token is d independent binary choices, as in the
+ * Infinity backbones of Sec. 4; entropy equation of Sec. 3.3 on the product distribution):
+ *   entropy[token] = sum_{i<d} h(softmax(bit_logits[token, i, 0], bit_logits[token, i, 1]))
+ * with h the binary entropy in nats, evaluated in fp32.  NaN logits give NaN.
+ *   bit_logits    [batch*rows_per_batch, d, 2] contiguous; dtype NOVA_F32 | NOVA_BF16
+ *   entropy       out [batch*rows_per_batch] fp32;  mean_entropy out [batch] fp32 or NULL
+ * d >= 1.  batch == 0 or rows_per_batch == 0 is a no-op.
+ */
+int nova_entropy_bits(nova_ctx* ctx, void* stream, const void* bit_logits, int logits_dtype,
+                      int64_t rows_per_batch, int batch, int d, float* entropy, float* mean_entropy);
+
+/*
  * Token entropy straight from a linear prediction head (Sec. 4, "Entropy Computation
  * Overhead": the distributions are the ones decoding produces; entropy equation of Sec. 3.3):
  *   logits = hidden W_head^T + b_head   (fp32 accumulation on the matrix cores, never stored)

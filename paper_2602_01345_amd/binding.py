@@ -77,6 +77,8 @@ def load_library() -> C.CDLL:
     lib.nova_workspace_bytes.restype = C.c_size_t
     lib.nova_entropy.argtypes = [vp, vp, vp, i32, i64, i32, i32, i64, vp, vp]
     lib.nova_select.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp]
+    lib.nova_entropy_bits.argtypes = [vp, vp, vp, i32, i64, i32, i32, vp, vp]
+    lib.nova_entropy_bits.restype = i32
     lib.nova_head_entropy_workspace_bytes.argtypes = [i64, i32, i32]
     lib.nova_head_entropy_workspace_bytes.restype = C.c_size_t
     lib.nova_head_entropy.argtypes = [vp, vp, vp, vp, vp, i32, i64, i32, i32, i32, vp, vp, vp, C.c_size_t]
@@ -208,6 +210,15 @@ class Nova:
         rc = self.lib.nova_entropy(self.ctx, _stream(), _ptr(logits), _dtype_code(logits), N, B, V,
                                    logits.stride(1), _ptr(entropy), _ptr(mean))
         self._check(rc, "nova_entropy")
+
+    # -- nova_entropy_bits ----------------------------------------------------------
+    def entropy_bits(self, bit_logits: torch.Tensor, entropy: torch.Tensor, mean: Optional[torch.Tensor] = None):
+        """bit_logits [B, N, d, 2] (f32|bf16) -> entropy [B, N] f32 (and mean [B] f32)."""
+        B, N, d, two = bit_logits.shape
+        assert two == 2
+        rc = self.lib.nova_entropy_bits(self.ctx, _stream(), _ptr(bit_logits), _dtype_code(bit_logits), N, B, d,
+                                        _ptr(entropy), _ptr(mean))
+        self._check(rc, "nova_entropy_bits")
 
     # -- nova_head_entropy ----------------------------------------------------------
     def head_entropy_workspace_bytes(self, rows_per_batch: int, batch: int, V: int) -> int:

@@ -186,6 +186,21 @@ int nova_entropy(nova_ctx* ctx, void* stream, const void* logits, int logits_dty
   return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
 }
 
+int nova_entropy_bits(nova_ctx* ctx, void* stream, const void* bit_logits, int logits_dtype,
+                      int64_t rows_per_batch, int batch, int d, float* entropy, float* mean_entropy) {
+  if (!ctx) return NOVA_ERR_INVALID_ARG;
+  if (!valid_dtype(logits_dtype)) return NOVA_ERR_UNSUPPORTED;
+  if (rows_per_batch < 0 || batch < 0 || d < 1) return NOVA_ERR_INVALID_ARG;
+  if (rows_per_batch == 0 || batch == 0) return NOVA_OK;
+  if (!bit_logits || !entropy) return NOVA_ERR_INVALID_ARG;
+  if (rows_per_batch * batch > ((int64_t)1 << 31) - 8) return NOVA_ERR_UNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(bit_logits) % esize(logits_dtype)) != 0) return NOVA_ERR_INVALID_ARG;
+  if (int rc = set_device(ctx)) return rc;
+  hipError_t e = launch_entropy_bits(static_cast<hipStream_t>(stream), bit_logits, logits_dtype, rows_per_batch,
+                                     batch, d, entropy, mean_entropy);
+  return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
+}
+
 size_t nova_head_entropy_workspace_bytes(int64_t rows_per_batch, int batch, int V) {
   if (rows_per_batch <= 0 || batch <= 0 || V < 1 || rows_per_batch * batch > ((int64_t)1 << 24)) return 0;
   return head_entropy_workspace_bytes((int)(rows_per_batch * batch), V);

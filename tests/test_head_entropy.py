@@ -1,6 +1,8 @@
 """Entropy straight from a linear head (Sec. 4, "Entropy Computation Overhead") against the oracle's
 composition entropy(hidden W^T + b).  Tolerance: the logits are fp32 sums of exact bf16 products
 (K <= 2304 terms), so |dH| <= 1e-4 |H| + 1e-5 covers accumulation order and the fp32 softmax sums."""
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -96,3 +98,51 @@ def test_head_entropy_argument_errors():
     h48 = torch.zeros(1, 4, 48, dtype=torch.bfloat16, device="cuda")
     with pytest.raises(NovaError):
         nova.head_entropy(h48, w[:, :48].contiguous(), None, H, ws)      # C % 64 != 0
+
+
+# ---------------------------------------------------------------------------------------------
+# bitwise token heads
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("B,N,d", [(1, 1, 1), (2, 100, 32), (3, 257, 13), (2, 4096, 32), (1, 1000, 64)])
+def test_entropy_bits_matches_oracle(dtype, B, N, d):
+    g = torch.Generator().manual_seed(B * 31 + N + d)
+    # per-token temperature: tokens from fully undecided to fully decided
+    x = torch.randn(B, N, d, 2, generator=g) * torch.exp(torch.rand(B, N, 1, 1, generator=g) * 8.0 - 4.0)
+    x = x.to(dtype)
+    H = torch.empty(B, N, dtype=torch.float32, device="cuda")
+    mean = torch.empty(B, dtype=torch.float32, device="cuda")
+    Hn.nova().entropy_bits(x.cuda(), H, mean)
+    torch.cuda.synchronize()
+    ref = O.bitwise_entropy(Hn.f64(x))
+    got = H.cpu().numpy()
+    assert np.all(np.abs(got - ref) <= 1e-5 * np.abs(ref) + 1e-7 * d)
+    assert np.allclose(mean.cpu().numpy(), ref.mean(axis=1), rtol=1e-5, atol=1e-6)
+
+
+@pytest.mark.gpu
+def test_entropy_bits_edge_values():
+    x = torch.zeros(1, 6, 4, 2)
+    x[0, 1, :, 1] = 300.0                       # certain bits
+    x[0, 2, 0, 0] = float("inf")                # an infinite logit: that bit is certain
+    x[0, 3, 1, 0] = float("-inf")
+    x[0, 4, 2, 1] = float("nan")                # NaN propagates to the token
+    x[0, 5, :, 0] = math.log(3.0)               # p = 1/4 on every bit
+    H = torch.empty(1, 6, dtype=torch.float32, device="cuda")
+    Hn.nova().entropy_bits(x.cuda(), H)
+    got = H.cpu().numpy()[0]
+    ln2 = math.log(2.0)
+    assert got[0] == pytest.approx(4 * ln2, rel=1e-6)
+    assert got[1] == 0.0
+    assert got[2] == pytest.approx(3 * ln2, rel=1e-6) and got[3] == pytest.approx(3 * ln2, rel=1e-6)
+    assert math.isnan(got[4])
+    assert got[5] == pytest.approx(-4 * (0.25 * math.log(0.25) + 0.75 * math.log(0.75)), rel=1e-6)
+    # unaligned base pointer (odd element offset): the scalar path
+    y = torch.randn(2 * 7 * 2 + 1, dtype=torch.bfloat16, device="cuda")
+    view = y[1:].view(1, 2, 7, 2)
+    H2 = torch.empty(1, 2, dtype=torch.float32, device="cuda")
+    Hn.nova().lib.nova_entropy_bits(Hn.nova().ctx, torch.cuda.current_stream().cuda_stream, view.data_ptr(), 1, 2, 1, 7,
+                                    H2.data_ptr(), None)
+    torch.cuda.synchronize()
+    assert np.allclose(H2.cpu().numpy(), O.bitwise_entropy(Hn.f64(view)), rtol=1e-5)
