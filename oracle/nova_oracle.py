@@ -29,6 +29,14 @@ What each function follows:
                              block, permutation equivariance, degenerate weights,
                              library second opinions) its parity is unpinned
                              against the paper.
+  pruned_block(variants)  -- the same block as the backbones of Sec. 4 build it: modulation of
+                             both norms and gating of both branches by per-image vectors
+                             (adaptive LayerNorm conditioning), unit-length queries and keys
+                             per head with a per-head score multiplier in place of 1/sqrt(dh),
+                             tanh-form GELU.  The paper names the backbones, not these
+                             details; the formulas are this build's reading (parity unpinned
+                             against the paper; pinned to reductions to the base block,
+                             invariances and library second opinions).
   bilinear_upsample,
   merge_cache             -- Cache_{t,j} = R_out - R_in, its interpolation to the
                              next grid and the reuse rule for pruned tokens (Sec. 3.3,
@@ -134,6 +142,20 @@ def gelu(x: np.ndarray) -> np.ndarray:
     return 0.5 * x * (1.0 + erf(x / np.sqrt(2.0)))
 
 
+def gelu_tanh(x: np.ndarray) -> np.ndarray:
+    """tanh-form GELU: 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3)))."""
+    return 0.5 * x * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (x + 0.044715 * x ** 3)))
+
+
+QK_NORM_EPS = 1e-12
+
+
+def unit_rows(a: np.ndarray) -> np.ndarray:
+    """Rows scaled to unit Euclidean length (a zero row stays zero: the divisor is floored at 1e-12)."""
+    n = np.sqrt(np.sum(a * a, axis=-1, keepdims=True))
+    return a / np.maximum(n, QK_NORM_EPS)
+
+
 def softmax(s: np.ndarray) -> np.ndarray:
     m = np.max(s, axis=-1, keepdims=True)
     e = np.exp(s - m)
@@ -144,8 +166,17 @@ def _f64(a):
     return None if a is None else np.asarray(a, dtype=np.float64)
 
 
-def pruned_block(x, idx, weights, k_prior, v_prior, heads):
+def pruned_block(x, idx, weights, k_prior, v_prior, heads, gelu_form="erf", qk_scale=None, ada=None):
     """One transformer block on the kept tokens only.
+
+    Variants (all off by default):
+      gelu_form  "erf" | "tanh"
+      qk_scale   [heads] or None.  When given, the query and key of every head are scaled to unit
+                 length, the scores are qk_scale[h] * <q^, k^> (no 1/sqrt(dh)), and the rows appended
+                 to the key cache are the unit-length keys (k_prior already holds such rows).
+      ada        [B, 6, C] or None: per-image (shift1, scale1, gate1, shift2, scale2, gate2).
+                 u = LN(xs) (1 + scale1) + shift1,  x1 = xs + gate1 * attn_branch,
+                 FFN input = LN(x1) (1 + scale2) + shift2,  y = x1 + gate2 * ffn_branch.
 
     x        [B, N, C]   block input (all tokens of the current scale)
     idx      [B, k]      kept token indices per batch row
@@ -168,25 +199,39 @@ def pruned_block(x, idx, weights, k_prior, v_prior, heads):
         b = W.get(name)
         return 0.0 if b is None else b
 
+    act = {"erf": gelu, "tanh": gelu_tanh}[gelu_form]
+    qk_scale = _f64(qk_scale)
+    ada = _f64(ada)
     y_kept = np.zeros((B, k, C))
     k_new = np.zeros((B, k, C))
     v_new = np.zeros((B, k, C))
     for b in range(B):
+        if ada is None:
+            shift1 = scale1 = shift2 = scale2 = 0.0
+            gate1 = gate2 = 1.0
+        else:
+            shift1, scale1, gate1, shift2, scale2, gate2 = ada[b]
         xs = x[b, idx[b]]                                 # gather kept rows  [k, C]
-        u = layer_norm(xs)
+        u = layer_norm(xs) * (1.0 + scale1) + shift1
         qkv = u @ W["w_qkv"].T + bias("b_qkv")
-        q, kk, vv = qkv[:, :C], qkv[:, C:2 * C], qkv[:, 2 * C:]
+        q, kk, vv = qkv[:, :C].copy(), qkv[:, C:2 * C].copy(), qkv[:, 2 * C:]
+        if qk_scale is not None:
+            for h in range(heads):
+                sl = slice(h * dh, (h + 1) * dh)
+                q[:, sl] = unit_rows(q[:, sl])
+                kk[:, sl] = unit_rows(kk[:, sl])
         k_new[b], v_new[b] = kk, vv
         Kc = np.concatenate([k_prior[b], kk], axis=0)     # [P + k, C]
         Vc = np.concatenate([v_prior[b], vv], axis=0)
         a = np.zeros((k, C))
         for h in range(heads):
             sl = slice(h * dh, (h + 1) * dh)
-            scores = (q[:, sl] @ Kc[:, sl].T) / np.sqrt(dh)   # [k, P + k], no mask inside the step
+            scores = q[:, sl] @ Kc[:, sl].T                   # [k, P + k], no mask inside the step
+            scores = scores / np.sqrt(dh) if qk_scale is None else scores * qk_scale[h]
             a[:, sl] = softmax(scores) @ Vc[:, sl]
-        x1 = xs + a @ W["w_o"].T + bias("b_o")
-        hdn = gelu(layer_norm(x1) @ W["w_fc1"].T + bias("b_fc1"))
-        y_kept[b] = x1 + hdn @ W["w_fc2"].T + bias("b_fc2")
+        x1 = xs + gate1 * (a @ W["w_o"].T + bias("b_o"))
+        hdn = act((layer_norm(x1) * (1.0 + scale2) + shift2) @ W["w_fc1"].T + bias("b_fc1"))
+        y_kept[b] = x1 + gate2 * (hdn @ W["w_fc2"].T + bias("b_fc2"))
     return y_kept, k_new, v_new
 
 

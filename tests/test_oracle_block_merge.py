@@ -270,3 +270,139 @@ def test_merge_rules():
     assert np.array_equal(outN, yall) and not np.isnan(cnN).any()
     outN2, _ = O.merge_cache(x, yall, allidx, None, hp, wp, h, w)
     assert np.array_equal(outN2, yall)
+
+
+# ---- block variants (conditioning by per-image vectors, unit-length q/k, tanh GELU) ---------
+def _rand_variant(rng, B, C, heads):
+    ada = rng.standard_normal((B, 6, C)) * 0.3
+    ada[:, 2] += 1.0
+    ada[:, 5] += 1.0                                   # gates around 1
+    qk_scale = rng.uniform(2.0, 12.0, size=heads)
+    return ada, qk_scale
+
+
+def test_variant_defaults_are_the_base_block_exactly():
+    rng = np.random.default_rng(20)
+    x, W, kp, vp = _rand_block(rng, B=2, N=9, P=4)
+    idx = np.array([[0, 1, 4, 8], [2, 3, 5, 6]])
+    base = O.pruned_block(x, idx, W, kp, vp, heads=2)
+    neutral = np.zeros((2, 6, 8)); neutral[:, 2] = 1.0; neutral[:, 5] = 1.0
+    for got in (O.pruned_block(x, idx, W, kp, vp, heads=2, gelu_form="erf", qk_scale=None, ada=None),
+                O.pruned_block(x, idx, W, kp, vp, heads=2, ada=neutral)):
+        for a, b in zip(got, base):
+            assert np.array_equal(a, b)
+
+
+def test_gelu_tanh_values_and_library():
+    v = np.array([-30.0, -3.0, -1.0, -1e-9, 0.0, 1e-9, 0.5, 1.0, 3.0, 30.0])
+    g = O.gelu_tanh(v)
+    assert g[4] == 0.0 and g[0] == 0.0 and g[-1] == 30.0
+    # x - gelu(x) = gelu(-x) * (-1): the two tails sum to the identity, g(x) - g(-x) = x
+    np.testing.assert_allclose(g - O.gelu_tanh(-v), v, rtol=1e-15, atol=1e-300)
+    np.testing.assert_allclose(g, F.gelu(torch.from_numpy(v), approximate="tanh").numpy(), rtol=1e-14, atol=1e-300)
+    # hand value at 1: 0.5 (1 + tanh(sqrt(2/pi) * 1.044715))
+    assert g[7] == pytest.approx(0.5 * (1.0 + math.tanh(math.sqrt(2.0 / math.pi) * 1.044715)), rel=1e-15)
+    # the two forms differ by at most ~5e-4 in absolute terms and they do differ
+    d = np.abs(O.gelu_tanh(np.linspace(-6, 6, 2001)) - O.gelu(np.linspace(-6, 6, 2001)))
+    assert 1e-4 < d.max() < 1e-3
+
+
+def test_variant_gates_and_modulation_reductions():
+    rng = np.random.default_rng(21)
+    x, W, kp, vp = _rand_block(rng, B=2, N=9, P=4)
+    idx = np.array([[0, 1, 4, 8], [2, 3, 5, 6]])
+    ada, _ = _rand_variant(rng, 2, 8, 2)
+    xs = np.stack([x[b, idx[b]] for b in range(2)])
+    # both gates 0: the block is the identity on the kept rows; K/V rows still come from the modulated norm
+    a0 = ada.copy(); a0[:, 2] = 0.0; a0[:, 5] = 0.0
+    y, kn, vn = O.pruned_block(x, idx, W, kp, vp, heads=2, ada=a0)
+    assert np.array_equal(y, xs)
+    for b in range(2):
+        u = O.layer_norm(xs[b]) * (1.0 + a0[b, 1]) + a0[b, 0]
+        qkv = u @ W["w_qkv"].T + W["b_qkv"]
+        np.testing.assert_allclose(kn[b], qkv[:, 8:16], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(vn[b], qkv[:, 16:], rtol=1e-12, atol=1e-14)
+    # the output is affine in each gate with the other parts fixed: gate2 enters only the last step
+    y1 = O.pruned_block(x, idx, W, kp, vp, heads=2, ada=ada)[0]
+    a2 = ada.copy(); a2[:, 5] *= 3.0
+    y3 = O.pruned_block(x, idx, W, kp, vp, heads=2, ada=a2)[0]
+    a_off = ada.copy(); a_off[:, 5] = 0.0
+    x1 = O.pruned_block(x, idx, W, kp, vp, heads=2, ada=a_off)[0]            # gate2 = 0 leaves x1
+    np.testing.assert_allclose(y3 - x1, 3.0 * (y1 - x1), rtol=1e-10, atol=1e-12)
+    # scale = -1 wipes the normalised input: with shift s the projections see the constant row s
+    a3 = ada.copy(); a3[:, 1] = -1.0
+    _, kn, _ = O.pruned_block(x, idx, W, kp, vp, heads=2, ada=a3)
+    for b in range(2):
+        ref = a3[b, 0] @ W["w_qkv"][8:16].T + W["b_qkv"][8:16]
+        np.testing.assert_allclose(kn[b], np.tile(ref, (4, 1)), rtol=1e-12, atol=1e-14)
+    # image b is modulated by ada[b] only
+    a4 = ada.copy(); a4[1] = rng.standard_normal((6, 8))
+    y4 = O.pruned_block(x, idx, W, kp, vp, heads=2, ada=a4)[0]
+    assert np.array_equal(y4[0], y1[0]) and not np.allclose(y4[1], y1[1])
+
+
+def test_variant_unit_length_queries_and_keys():
+    rng = np.random.default_rng(22)
+    x, W, kp, vp = _rand_block(rng, B=1, N=8, C=8, heads=2, P=3)
+    idx = np.array([[1, 2, 5, 7]])
+    qk_scale = np.array([4.0, 9.0])
+    kp = np.concatenate([O.unit_rows(kp[..., :4]), O.unit_rows(kp[..., 4:])], axis=-1)   # the cache holds unit keys
+    y, kn, vn = O.pruned_block(x, idx, W, kp, vp, heads=2, qk_scale=qk_scale)
+    for h in range(2):
+        np.testing.assert_allclose(np.linalg.norm(kn[0][:, h * 4:(h + 1) * 4], axis=-1), 1.0, rtol=1e-14)
+    # a positive rescaling of a head's query projection, or of its key projection, changes nothing
+    W2 = {n: (None if a is None else a.copy()) for n, a in W.items()}
+    W2["w_qkv"][0:4] *= 7.0; W2["b_qkv"][0:4] *= 7.0            # head 0 queries
+    W2["w_qkv"][12:16] *= 0.2; W2["b_qkv"][12:16] *= 0.2        # head 1 keys
+    y2, kn2, _ = O.pruned_block(x, idx, W2, kp, vp, heads=2, qk_scale=qk_scale)
+    np.testing.assert_allclose(y2, y, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(kn2, kn, rtol=1e-12, atol=1e-14)
+    # multiplier 0: every score is 0, attention is the plain mean of all value rows
+    y0, _, vn0 = O.pruned_block(x, idx, W, kp, vp, heads=2, qk_scale=np.zeros(2))
+    vmean = np.concatenate([vp[0], vn0[0]]).mean(axis=0)
+    xs = x[0, idx[0]]
+    x1 = xs + vmean @ W["w_o"].T + W["b_o"]
+    ref = x1 + O.gelu(O.layer_norm(x1) @ W["w_fc1"].T + W["b_fc1"]) @ W["w_fc2"].T + W["b_fc2"]
+    np.testing.assert_allclose(y0[0], ref, rtol=1e-11, atol=1e-13)
+    # a zero key row stays zero (no division by zero)
+    assert np.array_equal(O.unit_rows(np.zeros((2, 4))), np.zeros((2, 4)))
+
+
+@pytest.mark.parametrize("use_ada,use_qk,form", [(True, False, "erf"), (False, True, "erf"), (False, False, "tanh"),
+                                                 (True, True, "tanh")])
+def test_variant_library_second_opinion_torch_float64(use_ada, use_qk, form):
+    rng = np.random.default_rng(23)
+    C, heads, dh = 16, 4, 4
+    x, W, kp, vp = _rand_block(rng, B=2, N=12, C=C, heads=heads, P=5)
+    idx = np.array([[0, 2, 3, 7, 10, 11], [1, 2, 4, 5, 6, 9]])
+    ada, qk_scale = _rand_variant(rng, 2, C, heads)
+    if use_qk:
+        kp = O.unit_rows(kp.reshape(2, 5, heads, dh)).reshape(2, 5, C)
+    y, kn, vn = O.pruned_block(x, idx, W, kp, vp, heads=heads, gelu_form=form,
+                               qk_scale=qk_scale if use_qk else None, ada=ada if use_ada else None)
+    t = {n: torch.from_numpy(a) for n, a in W.items()}
+    hd = lambda a: a.reshape(a.shape[0], heads, dh).transpose(0, 1)          # [heads, rows, dh]
+    for b in range(2):
+        m = [torch.from_numpy(v) for v in ada[b]] if use_ada else [0.0, 0.0, 1.0, 0.0, 0.0, 1.0]
+        xs = torch.from_numpy(x[b, idx[b]])
+        u = torch.addcmul(m[0] + F.layer_norm(xs, (C,), eps=1e-6), F.layer_norm(xs, (C,), eps=1e-6), torch.as_tensor(m[1])) \
+            if use_ada else F.layer_norm(xs, (C,), eps=1e-6)
+        qkv = F.linear(u, t["w_qkv"], t["b_qkv"])
+        q, kk, vv = qkv.split(C, dim=-1)
+        qh, kh = hd(q), hd(kk)
+        if use_qk:
+            qh = F.normalize(qh, dim=-1) * torch.from_numpy(qk_scale)[:, None, None]
+            kh = F.normalize(kh, dim=-1)
+        K = torch.cat([hd(torch.from_numpy(kp[b])), kh], dim=1)
+        V = torch.cat([torch.from_numpy(vp[b]), vv])
+        a = F.scaled_dot_product_attention(qh, K, hd(V), scale=1.0 if use_qk else None)
+        a = a.transpose(0, 1).reshape(-1, C)
+        x1 = xs + m[2] * F.linear(a, t["w_o"], t["b_o"])
+        n2 = F.layer_norm(x1, (C,), eps=1e-6)
+        if use_ada:
+            n2 = n2 * (1.0 + m[4]) + m[3]
+        hdn = F.gelu(F.linear(n2, t["w_fc1"], t["b_fc1"]), approximate="tanh" if form == "tanh" else "none")
+        ref = x1 + m[5] * F.linear(hdn, t["w_fc2"], t["b_fc2"])
+        np.testing.assert_allclose(y[b], ref.numpy(), rtol=1e-9, atol=1e-11)
+        np.testing.assert_allclose(kn[b], kh.transpose(0, 1).reshape(-1, C).numpy(), rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(vn[b], vv.numpy(), rtol=1e-10, atol=1e-12)
