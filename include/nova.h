@@ -69,6 +69,25 @@ typedef struct nova_block_weights {
   const void* b_fc2; /* [C]                                                      */
 } nova_block_weights;
 
+/* Variations of the block that the backbones of Sec. 4 differ in (all off = the block documented at
+ * nova_pruned_block).  The paper names the backbones, not these details; the formulas are this library's.
+ *   gelu_tanh  0: erf GELU; 1: 0.5 v (1 + tanh(sqrt(2/pi) (v + 0.044715 v^3)))
+ *   qk_norm    0 | 1.  1: per head, q <- q / max(|q|, 1e-12), kk <- kk / max(|kk|, 1e-12) (Euclidean
+ *              length over dh), scores = qk_scale[head] * <q, k> instead of <q, k> / sqrt(dh); the rows
+ *              appended to k_cache are the unit-length keys and rows [0, P) are taken to be such rows
+ *   qk_scale   DEVICE fp32 [heads]; required when qk_norm, ignored otherwise
+ *   ada        NULL, or DEVICE [B, 6, C] in the activations' dtype, 16-byte aligned: per image
+ *              (shift1, scale1, gate1, shift2, scale2, gate2), used as
+ *                u  = LN(xs) (1 + scale1) + shift1        x1     = xs + gate1 * (a W_o^T + b_o)
+ *                u2 = LN(x1) (1 + scale2) + shift2        y_kept = x1 + gate2 * (GELU(u2 W_fc1^T + b_fc1) W_fc2^T + b_fc2)
+ */
+typedef struct nova_block_variant {
+  int32_t gelu_tanh;
+  int32_t qk_norm;
+  const float* qk_scale;
+  const void* ada;
+} nova_block_variant;
+
 /* Creates a context for HIP device `device_id` (queries its properties).
  * *out is a host object owned by the caller; release with nova_destroy. */
 int nova_create(nova_ctx** out, int device_id);
@@ -176,6 +195,14 @@ int nova_pruned_block(nova_ctx* ctx, void* stream, const nova_block_shape* shape
                       const nova_block_weights* weights, const void* x, const int32_t* kept_idx,
                       void* k_cache, void* v_cache, void* y_kept, void* workspace,
                       size_t workspace_bytes);
+
+/* nova_pruned_block with the block variations of `variant` (NULL = none: identical to
+ * nova_pruned_block).  Every other argument, requirement and error is as documented there;
+ * a non-zero flag other than 1 or a missing qk_scale is NOVA_ERR_INVALID_ARG. */
+int nova_pruned_block_variant(nova_ctx* ctx, void* stream, const nova_block_shape* shape,
+                              const nova_block_weights* weights, const nova_block_variant* variant,
+                              const void* x, const int32_t* kept_idx, void* k_cache, void* v_cache,
+                              void* y_kept, void* workspace, size_t workspace_bytes);
 
 /*
  * Residual cache reuse (Sec. 3.3, "Residual Cache Reuse", second and third equations):

@@ -34,6 +34,24 @@ class _Weights(C.Structure):
                 ("w_qkv", "b_qkv", "w_o", "b_o", "w_fc1", "b_fc1", "w_fc2", "b_fc2")]
 
 
+class _Variant(C.Structure):
+    _fields_ = [("gelu_tanh", C.c_int32), ("qk_norm", C.c_int32), ("qk_scale", C.c_void_p), ("ada", C.c_void_p)]
+
+
+@dataclass
+class BlockVariant:
+    """nova_block_variant: tanh GELU, unit-length q/k with a per-head multiplier (fp32 [heads], device),
+    per-image modulation and gates ([B, 6, C] in the activations' dtype, device)."""
+    gelu_tanh: bool = False
+    qk_scale: Optional[torch.Tensor] = None
+    ada: Optional[torch.Tensor] = None
+
+    def c_struct(self) -> "_Variant":
+        if self.qk_scale is not None:
+            assert self.qk_scale.dtype == torch.float32
+        return _Variant(int(self.gelu_tanh), int(self.qk_scale is not None), _ptr(self.qk_scale), _ptr(self.ada))
+
+
 @dataclass
 class BlockShape:
     dtype: int
@@ -85,6 +103,9 @@ def load_library() -> C.CDLL:
     lib.nova_head_entropy.restype = i32
     lib.nova_pruned_block.argtypes = [vp, vp, C.POINTER(_Shape), C.POINTER(_Weights), vp, vp, vp, vp, vp, vp,
                                       C.c_size_t]
+    lib.nova_pruned_block_variant.argtypes = [vp, vp, C.POINTER(_Shape), C.POINTER(_Weights), C.POINTER(_Variant),
+                                              vp, vp, vp, vp, vp, vp, C.c_size_t]
+    lib.nova_pruned_block_variant.restype = i32
     lib.nova_merge_cache.argtypes = [vp, vp, i32] + [i32] * 7 + [vp] * 7
     lib.nova_profile_stages.argtypes = [vp, C.c_uint32]
     lib.nova_profile_collect.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -256,6 +277,19 @@ class Nova:
                                         _ptr(k_cache), _ptr(v_cache), _ptr(y_kept), _ptr(workspace),
                                         workspace.numel() * workspace.element_size())
         self._check(rc, "nova_pruned_block")
+
+    def pruned_block_variant(self, shape: BlockShape, weights: Dict[str, Optional[torch.Tensor]],
+                             variant: Optional[BlockVariant], x: torch.Tensor, kept_idx: torch.Tensor,
+                             k_cache: torch.Tensor, v_cache: torch.Tensor, y_kept: torch.Tensor,
+                             workspace: torch.Tensor):
+        s = shape.c_struct()
+        w = _Weights(*[_ptr(weights.get(n)) for n, _ in _Weights._fields_])
+        v = variant.c_struct() if variant is not None else None
+        rc = self.lib.nova_pruned_block_variant(self.ctx, _stream(), C.byref(s), C.byref(w),
+                                                C.byref(v) if v is not None else None, _ptr(x), _ptr(kept_idx),
+                                                _ptr(k_cache), _ptr(v_cache), _ptr(y_kept), _ptr(workspace),
+                                                workspace.numel() * workspace.element_size())
+        self._check(rc, "nova_pruned_block_variant")
 
     # -- nova_merge_cache -----------------------------------------------------------
     def merge_cache(self, h: int, w: int, hp: int, wp: int, k: int, x: torch.Tensor,

@@ -253,7 +253,22 @@ int nova_layer_ratio(nova_ctx* ctx, void* stream, const float* mean_entropy, flo
 int nova_pruned_block(nova_ctx* ctx, void* stream, const nova_block_shape* shape,
                       const nova_block_weights* weights, const void* x, const int32_t* kept_idx, void* k_cache,
                       void* v_cache, void* y_kept, void* workspace, size_t workspace_bytes) {
+  return nova_pruned_block_variant(ctx, stream, shape, weights, nullptr, x, kept_idx, k_cache, v_cache, y_kept,
+                                   workspace, workspace_bytes);
+}
+
+int nova_pruned_block_variant(nova_ctx* ctx, void* stream, const nova_block_shape* shape,
+                              const nova_block_weights* weights, const nova_block_variant* variant,
+                              const void* x, const int32_t* kept_idx, void* k_cache, void* v_cache, void* y_kept,
+                              void* workspace, size_t workspace_bytes) {
   if (!ctx || !weights) return NOVA_ERR_INVALID_ARG;
+  nova_block_variant var = {0, 0, nullptr, nullptr};
+  if (variant) var = *variant;
+  if ((var.gelu_tanh != 0 && var.gelu_tanh != 1) || (var.qk_norm != 0 && var.qk_norm != 1))
+    return NOVA_ERR_INVALID_ARG;
+  if (var.qk_norm && (!var.qk_scale || (reinterpret_cast<uintptr_t>(var.qk_scale) & 3) != 0))
+    return NOVA_ERR_INVALID_ARG;
+  if (var.ada && !aligned16(var.ada)) return NOVA_ERR_INVALID_ARG;
   if (int rc = shape_error(shape)) return rc;
   if (shape->k == 0 || shape->B == 0) return NOVA_OK;
   if (!x || !kept_idx || !k_cache || !v_cache || !y_kept) return NOVA_ERR_INVALID_ARG;
@@ -270,9 +285,9 @@ int nova_pruned_block(nova_ctx* ctx, void* stream, const nova_block_shape* shape
   hipStream_t st = static_cast<hipStream_t>(stream);
   hipError_t e;
   if (shape->dtype == NOVA_BF16)
-    e = launch_block_bf16(ctx, st, *shape, *weights, x, kept_idx, k_cache, v_cache, y_kept, ws);
+    e = launch_block_bf16(ctx, st, *shape, *weights, var, x, kept_idx, k_cache, v_cache, y_kept, ws);
   else
-    e = launch_block_f32(ctx, st, *shape, *weights, static_cast<const float*>(x), kept_idx,
+    e = launch_block_f32(ctx, st, *shape, *weights, var, static_cast<const float*>(x), kept_idx,
                          static_cast<float*>(k_cache), static_cast<float*>(v_cache), static_cast<float*>(y_kept), ws);
   return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
 }

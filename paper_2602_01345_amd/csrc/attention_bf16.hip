@@ -394,14 +394,14 @@ hipError_t launch_cfg(const nova_ctx* ctx, hipStream_t st, const bf16_t* q, cons
 int attention_max_split() { return kMaxSplit; }
 
 hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void* qv, const void* kcv,
-                                 const void* vcv, int B, int k, int C, int heads, int cap, int kv_total, void* outv,
-                                 float* part_o, float* part_ml) {
+                                 const void* vcv, int B, int k, int C, int heads, int cap, int kv_total,
+                                 float score_scale, void* outv, float* part_o, float* part_ml) {
   const bf16_t* q = static_cast<const bf16_t*>(qv);
   const bf16_t* kc = static_cast<const bf16_t*>(kcv);
   const bf16_t* vc = static_cast<const bf16_t*>(vcv);
   bf16_t* out = static_cast<bf16_t*>(outv);
   const int dh = C / heads;
-  const float scale_log2 = 1.4426950408889634f / sqrtf((float)dh);
+  const float scale_log2 = 1.4426950408889634f * score_scale;
   // One group of 32 queries per wave (two workgroups per CU, so that one wave's softmax overlaps
   // another wave's MFMAs); two groups per wave (half the LDS reads per MFMA, one workgroup per
   // CU) can be forced for tuning.

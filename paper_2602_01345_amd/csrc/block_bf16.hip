@@ -4,6 +4,9 @@
 //   gather+LN -> QKV GEMM (epilogue appends K/V to the caches) -> flash-style attention
 //   -> O-proj GEMM (+ residual) -> LN -> FFN1 GEMM (+GELU) -> FFN2 GEMM (+ residual)
 //
+// Block variants (the backbones of Sec. 4): both norms modulated and both branches gated by per-image
+// vectors, queries and keys rescaled to unit length after the QKV GEMM, tanh-form GELU.
+//
 // The GEMMs live in gemm_bf16.hip, the attention kernel in attention_bf16.hip; this file only
 // sequences them on the caller's stream.
 #include "common.h"
@@ -11,8 +14,8 @@
 #include "nova_internal.h"
 
 hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_shape& s,
-                             const nova_block_weights& w, const void* xv, const int32_t* idx, void* kcv,
-                             void* vcv, void* yv, const BlockWorkspace& ws) {
+                             const nova_block_weights& w, const nova_block_variant& var, const void* xv,
+                             const int32_t* idx, void* kcv, void* vcv, void* yv, const BlockWorkspace& ws) {
   const int M = s.B * s.k, C = s.C, F = s.C * s.ffn_mult, dh = s.C / s.heads;
   const bf16_t* x = static_cast<const bf16_t*>(xv);
   bf16_t* kc = static_cast<bf16_t*>(kcv);
@@ -24,48 +27,58 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
   bf16_t* x1 = reinterpret_cast<bf16_t*>(ws.x1);
   bf16_t* hid = reinterpret_cast<bf16_t*>(ws.hid);
 
+  // per-image conditioning vectors [B, 6, C]: shift1, scale1, gate1, shift2, scale2, gate2
+  const bf16_t* ada = static_cast<const bf16_t*>(var.ada);
+  const int ada_pitch = 6 * C;
+  auto ada_row = [&](int j) { return ada ? ada + (int64_t)j * C : nullptr; };
+
   hipError_t e;
   {
     StageTimer t(ctx, st, NOVA_STAGE_GATHER_LN);
-    e = launch_gather_ln(st, NOVA_BF16, x, idx, M, s.k, s.N, C, u);
+    e = launch_gather_ln(st, NOVA_BF16, x, idx, M, s.k, s.N, C, ada_row(0), ada_row(1), ada_pitch, u);
   }
   if (e != hipSuccess) return e;
 
   EpiParams<bf16_t> ep = {};
   ep.C = C; ep.heads = s.heads; ep.dh = dh; ep.cap = s.kv_capacity; ep.P = s.kv_len; ep.k = s.k;
   ep.idx = idx; ep.Ntok = s.N;
+  ep.gate_pitch = ada_pitch; ep.gelu_tanh = var.gelu_tanh;
 
   ep.bias = static_cast<const bf16_t*>(w.b_qkv); ep.out = q; ep.ldo = C; ep.kc = kc; ep.vc = vc;
   {
     StageTimer t(ctx, st, NOVA_STAGE_QKV);
     e = launch_gemm_bf16(ctx, st, EPI_QKV, u, w.w_qkv, M, 3 * C, C, ep);
+    if (e == hipSuccess && var.qk_norm)
+      e = launch_qk_norm(st, NOVA_BF16, q, kc, var.qk_scale, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len);
   }
+  if (e != hipSuccess) return e;
 
   {
     StageTimer t(ctx, st, NOVA_STAGE_ATTENTION);
-    e = launch_attention_bf16(ctx, st, q, kc, vc, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len + s.k, attn,
+    e = launch_attention_bf16(ctx, st, q, kc, vc, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len + s.k,
+                              var.qk_norm ? 1.0f : 1.0f / sqrtf((float)dh), attn,
                               reinterpret_cast<float*>(ws.part_o), reinterpret_cast<float*>(ws.part_ml));
   }
   if (e != hipSuccess) return e;
 
-  ep.bias = static_cast<const bf16_t*>(w.b_o); ep.out = x1; ep.ldo = C; ep.res = x;
+  ep.bias = static_cast<const bf16_t*>(w.b_o); ep.out = x1; ep.ldo = C; ep.res = x; ep.gate = ada_row(2);
   {
     StageTimer t(ctx, st, NOVA_STAGE_OPROJ);
     e = launch_gemm_bf16(ctx, st, EPI_ATTN_OUT, attn, w.w_o, M, C, C, ep);
   }
   {
     StageTimer t(ctx, st, NOVA_STAGE_LN2);
-    e = launch_gather_ln(st, NOVA_BF16, x1, nullptr, M, s.k, s.N, C, u);
+    e = launch_gather_ln(st, NOVA_BF16, x1, nullptr, M, s.k, s.N, C, ada_row(3), ada_row(4), ada_pitch, u);
   }
   if (e != hipSuccess) return e;
 
-  ep.bias = static_cast<const bf16_t*>(w.b_fc1); ep.out = hid; ep.ldo = F;
+  ep.bias = static_cast<const bf16_t*>(w.b_fc1); ep.out = hid; ep.ldo = F; ep.gate = nullptr;
   {
     StageTimer t(ctx, st, NOVA_STAGE_FFN1);
     e = launch_gemm_bf16(ctx, st, EPI_GELU, u, w.w_fc1, M, F, C, ep);
   }
 
-  ep.bias = static_cast<const bf16_t*>(w.b_fc2); ep.out = y; ep.ldo = C; ep.res = x1;
+  ep.bias = static_cast<const bf16_t*>(w.b_fc2); ep.out = y; ep.ldo = C; ep.res = x1; ep.gate = ada_row(5);
   {
     StageTimer t(ctx, st, NOVA_STAGE_FFN2);
     e = launch_gemm_bf16(ctx, st, EPI_RESIDUAL, hid, w.w_fc2, M, C, F, ep);

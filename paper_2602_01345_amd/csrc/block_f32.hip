@@ -82,8 +82,8 @@ void gemm(hipStream_t st, const float* A, const float* W, int M, int Nout, int K
 }  // namespace
 
 hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shape& s, const nova_block_weights& w,
-                            const float* x, const int32_t* idx, float* kc, float* vc, float* y,
-                            const BlockWorkspace& ws) {
+                            const nova_block_variant& var, const float* x, const int32_t* idx, float* kc, float* vc,
+                            float* y, const BlockWorkspace& ws) {
   const int M = s.B * s.k, C = s.C, F = s.C * s.ffn_mult, dh = s.C / s.heads;
   float* u = reinterpret_cast<float*>(ws.u);
   float* q = reinterpret_cast<float*>(ws.q);
@@ -91,21 +91,31 @@ hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shap
   float* x1 = reinterpret_cast<float*>(ws.x1);
   float* hid = reinterpret_cast<float*>(ws.hid);
 
+  // per-image conditioning vectors [B, 6, C]: shift1, scale1, gate1, shift2, scale2, gate2
+  const float* ada = static_cast<const float*>(var.ada);
+  const int ada_pitch = 6 * C;
+  auto ada_row = [&](int j) { return ada ? ada + (int64_t)j * C : nullptr; };
+
   hipError_t e;
   {
     StageTimer t(ctx, st, NOVA_STAGE_GATHER_LN);
-    e = launch_gather_ln(st, NOVA_F32, x, idx, M, s.k, s.N, C, u);
+    e = launch_gather_ln(st, NOVA_F32, x, idx, M, s.k, s.N, C, ada_row(0), ada_row(1), ada_pitch, u);
   }
   if (e != hipSuccess) return e;
 
   EpiParams<float> ep = {};
   ep.C = C; ep.heads = s.heads; ep.dh = dh; ep.cap = s.kv_capacity; ep.P = s.kv_len; ep.k = s.k;
   ep.idx = idx; ep.Ntok = s.N;
+  ep.gate_pitch = ada_pitch; ep.gelu_tanh = var.gelu_tanh;
 
   ep.bias = static_cast<const float*>(w.b_qkv); ep.out = q; ep.ldo = C; ep.kc = kc; ep.vc = vc;
   {
     StageTimer t(ctx, st, NOVA_STAGE_QKV);
     gemm<EPI_QKV>(st, u, static_cast<const float*>(w.w_qkv), M, 3 * C, C, ep);
+    if (var.qk_norm) {
+      e = launch_qk_norm(st, NOVA_F32, q, kc, var.qk_scale, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len);
+      if (e != hipSuccess) return e;
+    }
   }
 
   const int kv_total = s.kv_len + s.k;
@@ -113,27 +123,27 @@ hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shap
   {
     StageTimer t(ctx, st, NOVA_STAGE_ATTENTION);
     attention_f32_kernel<<<dim3(M, s.heads), NOVA_WAVE, lds, st>>>(q, kc, vc, s.k, C, s.heads, dh, s.kv_capacity,
-                                                                   kv_total, 1.0f / sqrtf((float)dh), attn);
+                                                                   kv_total, var.qk_norm ? 1.0f : 1.0f / sqrtf((float)dh), attn);
   }
 
-  ep.bias = static_cast<const float*>(w.b_o); ep.out = x1; ep.ldo = C; ep.res = x;
+  ep.bias = static_cast<const float*>(w.b_o); ep.out = x1; ep.ldo = C; ep.res = x; ep.gate = ada_row(2);
   {
     StageTimer t(ctx, st, NOVA_STAGE_OPROJ);
     gemm<EPI_ATTN_OUT>(st, attn, static_cast<const float*>(w.w_o), M, C, C, ep);
   }
   {
     StageTimer t(ctx, st, NOVA_STAGE_LN2);
-    e = launch_gather_ln(st, NOVA_F32, x1, nullptr, M, s.k, s.N, C, u);
+    e = launch_gather_ln(st, NOVA_F32, x1, nullptr, M, s.k, s.N, C, ada_row(3), ada_row(4), ada_pitch, u);
   }
   if (e != hipSuccess) return e;
 
-  ep.bias = static_cast<const float*>(w.b_fc1); ep.out = hid; ep.ldo = F;
+  ep.bias = static_cast<const float*>(w.b_fc1); ep.out = hid; ep.ldo = F; ep.gate = nullptr;
   {
     StageTimer t(ctx, st, NOVA_STAGE_FFN1);
     gemm<EPI_GELU>(st, u, static_cast<const float*>(w.w_fc1), M, F, C, ep);
   }
 
-  ep.bias = static_cast<const float*>(w.b_fc2); ep.out = y; ep.ldo = C; ep.res = x1;
+  ep.bias = static_cast<const float*>(w.b_fc2); ep.out = y; ep.ldo = C; ep.res = x1; ep.gate = ada_row(5);
   {
     StageTimer t(ctx, st, NOVA_STAGE_FFN2);
     gemm<EPI_RESIDUAL>(st, hid, static_cast<const float*>(w.w_fc2), M, C, F, ep);

@@ -25,6 +25,11 @@ struct EpiParams {
   const T* res;         // EPI_ATTN_OUT: x [B, Ntok, C] gathered through idx; EPI_RESIDUAL: x1 [M, C]
   const int32_t* idx;   // [B, k]
   int Ntok;
+  // block variants: per-image gate on the projection before the residual is added (EPI_ATTN_OUT, EPI_RESIDUAL),
+  // gate[(row / k) * gate_pitch + col], nullptr = 1; tanh-form GELU instead of the erf form (EPI_GELU)
+  const T* gate;
+  int gate_pitch;
+  int gelu_tanh;
   // EPI_ENTROPY: [column tiles][M] partials (m, S, T, unused) with S = sum e^(x-m), T = sum (m-x) e^(x-m)
   f32x4* ent_part;
 };
@@ -44,6 +49,13 @@ __device__ __forceinline__ float gelu_erf(float v) {
   const float e = __builtin_amdgcn_exp2f(-x * x * 1.4426950408889634f);
   const float erf_abs = fmaf(-poly, e, 1.0f);               // erf(|v| / sqrt 2)
   return 0.5f * v * (1.0f + copysignf(erf_abs, v));
+}
+
+// tanh-form GELU 0.5 v (1 + tanh(z)), z = sqrt(2/pi) (v + 0.044715 v^3), written as v / (1 + e^(-2z)).
+__device__ __forceinline__ float gelu_tanh(float v) {
+  const float z = 0.7978845608028654f * fmaf(0.044715f * v * v, v, v);
+  const float e = __builtin_amdgcn_exp2f(-2.0f * 1.4426950408889634f * z);   // inf for very negative z: v / inf = -0
+  return v * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
 // Entropy partials of two disjoint column sets of one row, merged in place into the first:
@@ -79,10 +91,12 @@ __device__ __forceinline__ void epilogue_store(const EpiParams<T>& p, int row, i
   } else if (MODE == EPI_ATTN_OUT) {
     const int b = row / p.k;
     const int64_t srow = (int64_t)b * p.Ntok + min(max(p.idx[row], 0), p.Ntok - 1);
+    if (p.gate) v *= (float)p.gate[(int64_t)b * p.gate_pitch + col];
     p.out[(int64_t)row * p.ldo + col] = (T)(v + (float)p.res[srow * p.C + col]);
   } else if (MODE == EPI_GELU) {
-    p.out[(int64_t)row * p.ldo + col] = (T)gelu_erf(v);
+    p.out[(int64_t)row * p.ldo + col] = (T)(p.gelu_tanh ? gelu_tanh(v) : gelu_erf(v));
   } else {
+    if (p.gate) v *= (float)p.gate[(int64_t)(row / p.k) * p.gate_pitch + col];
     p.out[(int64_t)row * p.ldo + col] = (T)(v + (float)p.res[(int64_t)row * p.ldo + col]);
   }
 }

@@ -275,7 +275,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           float v = acc[i][jn][g4 * 4 + e] + bias[e];
-          if (MODE == EPI_GELU) v = gelu_erf(v);
+          if (MODE == EPI_GELU) v = ep.gelu_tanh ? gelu_tanh(v) : gelu_erf(v);
           o[e] = (bf16_t)v;
         }
         *reinterpret_cast<bf16x4*>(ct + lrw * CT_PITCH + lc) = o;
@@ -315,15 +315,21 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
         } else {
           int64_t rrow = row;
           int64_t rpitch = ep.ldo;
+          const int bb = row / ep.k;
           if (MODE == EPI_ATTN_OUT) {
-            const int bb = row / ep.k;
             rrow = (int64_t)bb * ep.Ntok + min(max(ep.idx[row], 0), ep.Ntok - 1);
             rpitch = ep.C;
           }
           const bf16x8 rs = *reinterpret_cast<const bf16x8*>(ep.res + rrow * rpitch + col);
           bf16x8 o;
+          if (ep.gate) {
+            const bf16x8 gt = *reinterpret_cast<const bf16x8*>(ep.gate + (int64_t)bb * ep.gate_pitch + col);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) o[e] = (bf16_t)((float)v[e] + (float)rs[e]);
+            for (int e = 0; e < 8; ++e) o[e] = (bf16_t)fmaf((float)gt[e], (float)v[e], (float)rs[e]);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (bf16_t)((float)v[e] + (float)rs[e]);
+          }
           *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + col) = o;
         }
       }

@@ -1,5 +1,5 @@
 // Row gather + LayerNorm (no affine, biased variance, eps 1e-6) feeding the block's
-// two projections.  One wave64 per row; mean and variance are two separate fp32
+// two projections; optionally modulated per image, LN(x) (1 + scale[b]) + shift[b].  One wave64 per row; mean and variance are two separate fp32
 // passes over the row (the second and third read hit the cache), the output is
 // rounded once to the storage type.
 #include "common.h"
@@ -13,7 +13,7 @@ constexpr float kEps = 1e-6f;
 template <typename T>
 __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void gather_ln_kernel(
     const T* __restrict__ src, const int32_t* __restrict__ idx, int M, int k, int N, int C,
-    T* __restrict__ dst) {
+    const T* __restrict__ shift, const T* __restrict__ scale, int mod_pitch, T* __restrict__ dst) {
   using VT = Vec16<T>;
   constexpr int VN = VT::N;
   const int lane = threadIdx.x & (NOVA_WAVE - 1);
@@ -43,6 +43,17 @@ __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void gather_ln_kernel(
     for (int e = 0; e < VN; ++e) { float d = v.get(e) - mean; sq = fmaf(d, d, sq); }
   }
   const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)C + kEps);
+  if (shift) {          // modulation vectors of image m / k (both given or neither)
+    const T* sh = shift + (int64_t)(m / k) * mod_pitch;
+    const T* sc = scale + (int64_t)(m / k) * mod_pitch;
+    for (int vi = lane; vi < nvec; vi += NOVA_WAVE) {
+      VT v, o, a, g; v.load(p + vi * VN); a.load(sh + vi * VN); g.load(sc + vi * VN);
+#pragma unroll
+      for (int e = 0; e < VN; ++e) o.set(e, fmaf((v.get(e) - mean) * rstd, 1.0f + g.get(e), a.get(e)));
+      o.store(q + vi * VN);
+    }
+    return;
+  }
   for (int vi = lane; vi < nvec; vi += NOVA_WAVE) {
     VT v, o; v.load(p + vi * VN);
 #pragma unroll
@@ -54,13 +65,15 @@ __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void gather_ln_kernel(
 }  // namespace
 
 hipError_t launch_gather_ln(hipStream_t st, int dtype, const void* src, const int32_t* idx, int M, int k,
-                            int N, int C, void* dst) {
+                            int N, int C, const void* shift, const void* scale, int mod_pitch, void* dst) {
   const unsigned grid = (unsigned)((M + kWavesPerBlock - 1) / kWavesPerBlock);
   if (dtype == NOVA_BF16)
     gather_ln_kernel<bf16_t><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(
-        static_cast<const bf16_t*>(src), idx, M, k, N, C, static_cast<bf16_t*>(dst));
+        static_cast<const bf16_t*>(src), idx, M, k, N, C, static_cast<const bf16_t*>(shift),
+        static_cast<const bf16_t*>(scale), mod_pitch, static_cast<bf16_t*>(dst));
   else
     gather_ln_kernel<float><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(
-        static_cast<const float*>(src), idx, M, k, N, C, static_cast<float*>(dst));
+        static_cast<const float*>(src), idx, M, k, N, C, static_cast<const float*>(shift),
+        static_cast<const float*>(scale), mod_pitch, static_cast<float*>(dst));
   return hipGetLastError();
 }

@@ -79,13 +79,18 @@ struct BlockWorkspace {
 BlockWorkspace carve_workspace(const nova_block_shape& s, void* base);
 
 // norm.hip: dst[m] = LayerNorm(src[row(m)]); with idx, row(m) = (m / k) * N + idx[m], else row(m) = m
+// shift / scale: per-image modulation vectors (image = m / k, row pitch mod_pitch elements), both or neither
 hipError_t launch_gather_ln(hipStream_t st, int dtype, const void* src, const int32_t* idx, int M, int k,
-                            int N, int C, void* dst);
+                            int N, int C, const void* shift, const void* scale, int mod_pitch, void* dst);
+// qk_norm.hip: queries [B*k, C] and the cache's key rows [P, P+k) scaled to unit length per head, in place;
+// the queries are also multiplied by qk_scale[head]
+hipError_t launch_qk_norm(hipStream_t st, int dtype, void* q, void* kc, const float* qk_scale, int B, int k, int C,
+                          int heads, int cap, int P);
 
 // block_f32.hip: plain fp32 kernels (correctness path for small fp32 models)
 hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shape& s, const nova_block_weights& w,
-                            const float* x, const int32_t* idx, float* kc, float* vc, float* y,
-                            const BlockWorkspace& ws);
+                            const nova_block_variant& var, const float* x, const int32_t* idx, float* kc, float* vc,
+                            float* y, const BlockWorkspace& ws);
 // gemm_bf16.hip: out = epilogue(A W^T) on the matrix cores; mode is an EpiMode
 template <typename T> struct EpiParams;
 hipError_t launch_gemm_bf16(const nova_ctx* ctx, hipStream_t st, int mode, const void* A, const void* W, int M,
@@ -95,14 +100,14 @@ size_t head_entropy_workspace_bytes(int M, int V);
 hipError_t launch_head_entropy(const nova_ctx* ctx, hipStream_t st, const void* hidden, const void* w_head,
                                const void* b_head, int rows_per_batch, int batch, int C, int V, float* H,
                                float* mean, void* workspace);
-// attention_bf16.hip: attn[B*k, C] = softmax(q K^T / sqrt(dh)) V per head over kv_total cached keys
+// attention_bf16.hip: attn[B*k, C] = softmax(score_scale * q K^T) V per head over kv_total cached keys
 // part_o / part_ml: workspace for split-key partial results ([max_split, B*k, C] and [max_split, B*k, heads, 2]
 // fp32), or nullptr to forbid splitting
 int attention_max_split();
 hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void* q, const void* kc, const void* vc,
-                                 int B, int k, int C, int heads, int cap, int kv_total, void* out, float* part_o,
-                                 float* part_ml);
+                                 int B, int k, int C, int heads, int cap, int kv_total, float score_scale, void* out,
+                                 float* part_o, float* part_ml);
 // block_bf16.hip: MFMA path
 hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_shape& s,
-                             const nova_block_weights& w, const void* x, const int32_t* idx, void* kc,
-                             void* vc, void* y, const BlockWorkspace& ws);
+                             const nova_block_weights& w, const nova_block_variant& var, const void* x,
+                             const int32_t* idx, void* kc, void* vc, void* y, const BlockWorkspace& ws);

@@ -1,0 +1,53 @@
+// Unit-length queries and keys (a block variant of the backbones in Sec. 4: cosine-similarity
+// attention with a per-head multiplier).  After the QKV projection has written the queries to the
+// workspace and appended the keys to the cache, one wave per (kept row, head) rescales both in place:
+//   q <- qk_scale[head] * q / max(|q|, 1e-12),   k <- k / max(|k|, 1e-12)
+// so that the attention kernel runs unchanged with a score multiplier of 1.  Norms in fp32.
+#include "common.h"
+#include "nova_internal.h"
+
+namespace {
+
+constexpr int kWavesPerBlock = 4;
+constexpr float kNormFloor = 1e-12f;
+
+template <typename T>
+__global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void qk_norm_kernel(
+    T* __restrict__ q, T* __restrict__ kc, const float* __restrict__ qk_scale, int M, int k, int C, int heads,
+    int dh, int cap, int P) {
+  const int lane = threadIdx.x & (NOVA_WAVE - 1);
+  const int64_t item = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / NOVA_WAVE;   // (row m, head)
+  if (item >= (int64_t)M * heads) return;
+  const int m = (int)(item / heads), head = (int)(item - (int64_t)m * heads);
+  const int b = m / k, s = m - b * k;
+  T* qp = q + (int64_t)m * C + head * dh;
+  T* kp = kc + (((int64_t)b * heads + head) * cap + P + s) * dh;
+  float sq = 0.f, sk = 0.f;
+  for (int d = lane; d < dh; d += NOVA_WAVE) {
+    const float a = (float)qp[d], c = (float)kp[d];
+    sq = fmaf(a, a, sq);
+    sk = fmaf(c, c, sk);
+  }
+  const float fq = qk_scale[head] / fmaxf(sqrtf(wave_sum(sq)), kNormFloor);
+  const float fk = 1.0f / fmaxf(sqrtf(wave_sum(sk)), kNormFloor);
+  for (int d = lane; d < dh; d += NOVA_WAVE) {
+    qp[d] = (T)((float)qp[d] * fq);
+    kp[d] = (T)((float)kp[d] * fk);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_qk_norm(hipStream_t st, int dtype, void* q, void* kc, const float* qk_scale, int B, int k, int C,
+                          int heads, int cap, int P) {
+  const int M = B * k, dh = C / heads;
+  const int64_t items = (int64_t)M * heads;
+  const unsigned grid = (unsigned)((items + kWavesPerBlock - 1) / kWavesPerBlock);
+  if (dtype == NOVA_BF16)
+    qk_norm_kernel<bf16_t><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(
+        static_cast<bf16_t*>(q), static_cast<bf16_t*>(kc), qk_scale, M, k, C, heads, dh, cap, P);
+  else
+    qk_norm_kernel<float><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(
+        static_cast<float*>(q), static_cast<float*>(kc), qk_scale, M, k, C, heads, dh, cap, P);
+  return hipGetLastError();
+}

@@ -11,7 +11,7 @@ from typing import Dict, List, Optional
 
 import torch
 
-from .binding import NOVA_BF16, NOVA_F32, BlockShape, Nova
+from .binding import NOVA_BF16, NOVA_F32, BlockShape, BlockVariant, Nova
 
 
 @dataclass
@@ -29,6 +29,7 @@ class BlockState:
     y_kept: torch.Tensor = None          # [B, k, C]
     out: torch.Tensor = None             # [B, N, C]
     cache_new: torch.Tensor = None       # [B, N, C]
+    variant: Optional[BlockVariant] = None   # block variations (nova_pruned_block_variant); None = the base block
 
 
 class StepRunner:
@@ -66,8 +67,12 @@ class StepRunner:
         n = self.nova
         n.entropy(st.logits, st.entropy)
         n.select(st.entropy, st.k, st.kept_idx, st.keep_mask)
-        n.pruned_block(self.shape(st.k), st.weights, x, st.kept_idx, st.k_cache, st.v_cache, st.y_kept,
-                       self._workspace)
+        if st.variant is None:
+            n.pruned_block(self.shape(st.k), st.weights, x, st.kept_idx, st.k_cache, st.v_cache, st.y_kept,
+                           self._workspace)
+        else:
+            n.pruned_block_variant(self.shape(st.k), st.weights, st.variant, x, st.kept_idx, st.k_cache,
+                                   st.v_cache, st.y_kept, self._workspace)
         n.merge_cache(self.grid, self.grid, self.prev_grid, self.prev_grid, st.k, x, st.y_kept, st.kept_idx,
                       st.keep_mask, st.cache_prev, st.out, st.cache_new)
         return st.out

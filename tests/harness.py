@@ -10,7 +10,7 @@ import torch
 
 import workloads as WL
 from oracle import nova_oracle as O
-from paper_2602_01345_amd import Nova, pack_k_cache, pack_v_cache, unpack_k_rows, unpack_v_rows
+from paper_2602_01345_amd import BlockVariant, Nova, pack_k_cache, pack_v_cache, unpack_k_rows, unpack_v_rows
 from paper_2602_01345_amd.step import BlockState, StepRunner
 
 ENTROPY_RTOL, ENTROPY_ATOL = 1e-5, 1e-7     # fp32 entropies: |dH| <= 1e-5 |H| + 1e-7
@@ -58,13 +58,32 @@ class HostBlock:
     k_prior: torch.Tensor
     v_prior: torch.Tensor
     cache_prev: torch.Tensor
+    # block variations: any of "gelu_tanh" (bool), "qk_scale" ([heads] fp32), "ada" ([B, 6, C]); None = base block
+    variant: Optional[Dict[str, object]] = None
 
 
-def make_host_block(wl: WL.Workload, j: int, scale: Optional[WL.Scale] = None, k: Optional[int] = None) -> HostBlock:
+def make_host_block(wl: WL.Workload, j: int, scale: Optional[WL.Scale] = None, k: Optional[int] = None,
+                    variant: Optional[set] = None) -> HostBlock:
+    """`variant`: a subset of {"gelu_tanh", "qk_norm", "ada"} switching block variations on."""
     s = scale or wl.last
     kp, vp = WL.make_kv_prior(wl, j, s)
+    var = None
+    if variant:
+        gen = WL.make_block_variant(wl, j)
+        var = {}
+        if "gelu_tanh" in variant:
+            var["gelu_tanh"] = True
+        if "ada" in variant:
+            var["ada"] = gen["ada"]
+        if "qk_norm" in variant:
+            var["qk_scale"] = gen["qk_scale"]
+            # the cache of such a model holds unit-length keys: rescale the generated prior rows per head
+            # (in float32, stored back in the workload's dtype; both sides then read the same stored rows)
+            B, P, C = kp.shape
+            kh = kp.to(torch.float32).reshape(B, P, wl.heads, C // wl.heads)
+            kp = torch.nn.functional.normalize(kh, dim=-1).reshape(B, P, C).to(kp.dtype)
     return HostBlock(wl, s, wl.k(j, s) if k is None else k, WL.make_logits(wl, j, s), WL.make_x(wl, s),
-                     WL.make_weights(wl, j), kp, vp, WL.make_cache_prev(wl, j, s))
+                     WL.make_weights(wl, j), kp, vp, WL.make_cache_prev(wl, j, s), var)
 
 
 def to_gpu(hb: HostBlock, poison: bool = False):
@@ -80,6 +99,11 @@ def to_gpu(hb: HostBlock, poison: bool = False):
         k_cache=pack_k_cache(hb.k_prior.to(dev), wl.heads, cap, fill),
         v_cache=pack_v_cache(hb.v_prior.to(dev), wl.heads, cap, fill),
         cache_prev=hb.cache_prev.to(dev))
+    if hb.variant is not None:
+        qs, ada = hb.variant.get("qk_scale"), hb.variant.get("ada")
+        st.variant = BlockVariant(gelu_tanh=bool(hb.variant.get("gelu_tanh", False)),
+                                  qk_scale=None if qs is None else qs.to(dev),
+                                  ada=None if ada is None else ada.to(dev))
     runner.add_block(st)
     return runner, st, hb.x.to(dev)
 
@@ -92,7 +116,14 @@ def oracle_block(hb: HostBlock, H32: np.ndarray, rows=None):
     idx, mask = O.select(np.asarray(H32)[rows], hb.k)
     W = {n: f64(t) for n, t in hb.weights.items()}
     x = sel(hb.x)
-    y, kn, vn = O.pruned_block(x, idx[:, :hb.k], W, sel(hb.k_prior), sel(hb.v_prior), wl.heads)
+    kw = {}
+    if hb.variant is not None:
+        kw["gelu_form"] = "tanh" if hb.variant.get("gelu_tanh", False) else "erf"
+        if hb.variant.get("qk_scale") is not None:
+            kw["qk_scale"] = f64(hb.variant["qk_scale"])
+        if hb.variant.get("ada") is not None:
+            kw["ada"] = sel(hb.variant["ada"])
+    y, kn, vn = O.pruned_block(x, idx[:, :hb.k], W, sel(hb.k_prior), sel(hb.v_prior), wl.heads, **kw)
     out, cn = O.merge_cache(x, y, idx[:, :hb.k], sel(hb.cache_prev), s.prev_grid, s.prev_grid, s.grid, s.grid)
     return dict(idx=idx, mask=mask, y=y, k_new=kn, v_new=vn, out=out, cache_new=cn)
 

@@ -132,7 +132,7 @@ WORKLOADS: Dict[str, Workload] = {
 _TENSOR_IDS = {
     "logits": 1, "temperature": 2, "x": 3, "k_cache": 4, "v_cache": 5, "cache_prev": 6,
     "w_qkv": 10, "b_qkv": 11, "w_o": 12, "b_o": 13, "w_fc1": 14, "b_fc1": 15,
-    "w_fc2": 16, "b_fc2": 17,
+    "w_fc2": 16, "b_fc2": 17, "ada": 20, "qk_scale": 21,
 }
 
 
@@ -198,6 +198,19 @@ def make_weights(wl: Workload, block: int) -> Dict[str, torch.Tensor]:
         "w_fc1": (F, C), "b_fc1": (F,), "w_fc2": (C, F), "b_fc2": (C,),
     }
     return {n: _normal(wl.seed, n, block, 0, shp, 0.02, wl.dtype) for n, shp in shapes.items()}
+
+
+def make_block_variant(wl: Workload, block: int) -> Dict[str, torch.Tensor]:
+    """Inputs of the block variants: per-image conditioning vectors `ada` [B, 6, C] (shift1, scale1,
+    gate1, shift2, scale2, gate2; shifts and scales N(0, 0.2^2), gates 1 + N(0, 0.2^2)) in the
+    workload's dtype, and the per-head score multiplier `qk_scale` [heads] fp32, uniform in [4, 16]."""
+    g = _rng(wl.seed, "ada", block, 0)
+    ada = g.standard_normal(size=(wl.B, 6, wl.C), dtype=np.float32) * np.float32(0.2)
+    ada[:, 2] += np.float32(1.0)
+    ada[:, 5] += np.float32(1.0)
+    gs = _rng(wl.seed, "qk_scale", block, 0)
+    qk_scale = gs.uniform(4.0, 16.0, size=(wl.heads,)).astype(np.float32)
+    return {"ada": torch.from_numpy(ada).to(torch_dtype(wl.dtype)), "qk_scale": torch.from_numpy(qk_scale)}
 
 
 def small_variant(wl: Workload, B: int | None = None, L: int | None = None) -> Workload:
