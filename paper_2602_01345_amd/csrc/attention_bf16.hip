@@ -32,7 +32,6 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-constexpr int ATT_WAVES = 4;
 constexpr int BKV = 64;              // keys per tile
 constexpr int kMaxSplit = 4;         // most key splits a launch may use (sizes the partial-result workspace)
 

@@ -42,7 +42,7 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
   EpiParams<bf16_t> ep = {};
   ep.C = C; ep.heads = s.heads; ep.dh = dh; ep.cap = s.kv_capacity; ep.P = s.kv_len; ep.k = s.k;
   ep.idx = idx; ep.Ntok = s.N;
-  ep.gate_pitch = ada_pitch; ep.gelu_tanh = var.gelu_tanh;
+  ep.gate_pitch = ada_pitch;
 
   ep.bias = static_cast<const bf16_t*>(w.b_qkv); ep.out = q; ep.ldo = C; ep.kc = kc; ep.vc = vc;
   {
@@ -75,7 +75,7 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
   ep.bias = static_cast<const bf16_t*>(w.b_fc1); ep.out = hid; ep.ldo = F; ep.gate = nullptr;
   {
     StageTimer t(ctx, st, NOVA_STAGE_FFN1);
-    e = launch_gemm_bf16(ctx, st, EPI_GELU, u, w.w_fc1, M, F, C, ep);
+    e = launch_gemm_bf16(ctx, st, var.gelu_tanh ? EPI_GELU_TANH : EPI_GELU, u, w.w_fc1, M, F, C, ep);
   }
 
   ep.bias = static_cast<const bf16_t*>(w.b_fc2); ep.out = y; ep.ldo = C; ep.res = x1; ep.gate = ada_row(5);

@@ -106,7 +106,7 @@ hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shap
   EpiParams<float> ep = {};
   ep.C = C; ep.heads = s.heads; ep.dh = dh; ep.cap = s.kv_capacity; ep.P = s.kv_len; ep.k = s.k;
   ep.idx = idx; ep.Ntok = s.N;
-  ep.gate_pitch = ada_pitch; ep.gelu_tanh = var.gelu_tanh;
+  ep.gate_pitch = ada_pitch;
 
   ep.bias = static_cast<const float*>(w.b_qkv); ep.out = q; ep.ldo = C; ep.kc = kc; ep.vc = vc;
   {
@@ -140,7 +140,8 @@ hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shap
   ep.bias = static_cast<const float*>(w.b_fc1); ep.out = hid; ep.ldo = F; ep.gate = nullptr;
   {
     StageTimer t(ctx, st, NOVA_STAGE_FFN1);
-    gemm<EPI_GELU>(st, u, static_cast<const float*>(w.w_fc1), M, F, C, ep);
+    if (var.gelu_tanh) gemm<EPI_GELU_TANH>(st, u, static_cast<const float*>(w.w_fc1), M, F, C, ep);
+    else gemm<EPI_GELU>(st, u, static_cast<const float*>(w.w_fc1), M, F, C, ep);
   }
 
   ep.bias = static_cast<const float*>(w.b_fc2); ep.out = y; ep.ldo = C; ep.res = x1; ep.gate = ada_row(5);

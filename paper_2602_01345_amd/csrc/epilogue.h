@@ -9,7 +9,8 @@ enum EpiMode {
   EPI_ATTN_OUT = 1,   // x1 = x[gathered row] + acc + b_o
   EPI_GELU = 2,       // hid = GELU(acc + b_fc1), erf form
   EPI_RESIDUAL = 3,   // y = x1 + acc + b_fc2
-  EPI_ENTROPY = 4     // acc + b are logits: only per-row softmax-entropy partials of the tile's columns leave the kernel
+  EPI_ENTROPY = 4,    // acc + b are logits: only per-row softmax-entropy partials of the tile's columns leave the kernel
+  EPI_GELU_TANH = 5   // EPI_GELU with the tanh form
 };
 
 template <typename T>
@@ -26,10 +27,9 @@ struct EpiParams {
   const int32_t* idx;   // [B, k]
   int Ntok;
   // block variants: per-image gate on the projection before the residual is added (EPI_ATTN_OUT, EPI_RESIDUAL),
-  // gate[(row / k) * gate_pitch + col], nullptr = 1; tanh-form GELU instead of the erf form (EPI_GELU)
+  // gate[(row / k) * gate_pitch + col], nullptr = 1
   const T* gate;
   int gate_pitch;
-  int gelu_tanh;
   // EPI_ENTROPY: [column tiles][M] partials (m, S, T, unused) with S = sum e^(x-m), T = sum (m-x) e^(x-m)
   f32x4* ent_part;
 };
@@ -94,7 +94,9 @@ __device__ __forceinline__ void epilogue_store(const EpiParams<T>& p, int row, i
     if (p.gate) v *= (float)p.gate[(int64_t)b * p.gate_pitch + col];
     p.out[(int64_t)row * p.ldo + col] = (T)(v + (float)p.res[srow * p.C + col]);
   } else if (MODE == EPI_GELU) {
-    p.out[(int64_t)row * p.ldo + col] = (T)(p.gelu_tanh ? gelu_tanh(v) : gelu_erf(v));
+    p.out[(int64_t)row * p.ldo + col] = (T)gelu_erf(v);
+  } else if (MODE == EPI_GELU_TANH) {
+    p.out[(int64_t)row * p.ldo + col] = (T)gelu_tanh(v);
   } else {
     if (p.gate) v *= (float)p.gate[(int64_t)(row / p.k) * p.gate_pitch + col];
     p.out[(int64_t)row * p.ldo + col] = (T)(v + (float)p.res[(int64_t)row * p.ldo + col]);

@@ -275,7 +275,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           float v = acc[i][jn][g4 * 4 + e] + bias[e];
-          if (MODE == EPI_GELU) v = ep.gelu_tanh ? gelu_tanh(v) : gelu_erf(v);
+          if (MODE == EPI_GELU) v = gelu_erf(v);
+          if (MODE == EPI_GELU_TANH) v = gelu_tanh(v);
           o[e] = (bf16_t)v;
         }
         *reinterpret_cast<bf16x4*>(ct + lrw * CT_PITCH + lc) = o;
@@ -310,7 +311,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
             const int bb = row / ep.k, s = row - bb * ep.k;
             *reinterpret_cast<bf16x8*>(ep.kc + (((int64_t)bb * ep.heads + head) * ep.cap + ep.P + s) * ep.dh + d) = v;
           }
-        } else if (MODE == EPI_GELU) {
+        } else if (MODE == EPI_GELU || MODE == EPI_GELU_TANH) {
           *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + col) = v;
         } else {
           int64_t rrow = row;
@@ -440,6 +441,7 @@ hipError_t launch_gemm_bf16(const nova_ctx* ctx, hipStream_t st, int mode, const
     case EPI_QKV: return launch_mode<EPI_QKV>(ctx, st, a, w, M, Nout, K, ep);
     case EPI_ATTN_OUT: return launch_mode<EPI_ATTN_OUT>(ctx, st, a, w, M, Nout, K, ep);
     case EPI_GELU: return launch_mode<EPI_GELU>(ctx, st, a, w, M, Nout, K, ep);
+    case EPI_GELU_TANH: return launch_mode<EPI_GELU_TANH>(ctx, st, a, w, M, Nout, K, ep);
     case EPI_ENTROPY: return launch_mode<EPI_ENTROPY>(ctx, st, a, w, M, Nout, K, ep);
     default: return launch_mode<EPI_RESIDUAL>(ctx, st, a, w, M, Nout, K, ep);
   }
