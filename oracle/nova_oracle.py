@@ -41,6 +41,10 @@ What each function follows:
   merge_cache             -- Cache_{t,j} = R_out - R_in, its interpolation to the
                              next grid and the reuse rule for pruned tokens (Sec. 3.3,
                              Residual Cache Reuse, second and third equations).
+  nearest_upsample,
+  bicubic_upsample        -- other interpolation kernels for the same step (the paper says
+                             only that the cache is interpolated): nearest cell, and cubic
+                             convolution with a = -0.75 as image libraries define it.
 
 Readings taken where the paper is silent are listed in the repository's design
 notes; the ones that matter here: ties in entropy keep the lower index; NaN
@@ -261,8 +265,63 @@ def bilinear_upsample(cache_prev, hp: int, wp: int, h: int, w: int) -> np.ndarra
     return out.reshape(B, h * w, C)
 
 
-def merge_cache(x, y_kept, idx, cache_prev, hp, wp, h, w):
+def nearest_upsample(cache_prev, hp: int, wp: int, h: int, w: int) -> np.ndarray:
+    """Nearest source cell of each output cell centre: index min(floor((dst + 0.5) n_in / n_out), n_in - 1)."""
+    c = _f64(cache_prev)
+    B, _, C = c.shape
+    c = c.reshape(B, hp, wp, C)
+    iy = np.minimum(np.floor((np.arange(h) + 0.5) * (hp / h)).astype(np.int64), hp - 1)
+    ix = np.minimum(np.floor((np.arange(w) + 0.5) * (wp / w)).astype(np.int64), wp - 1)
+    return c[:, iy][:, :, ix].reshape(B, h * w, C)
+
+
+CUBIC_A = -0.75
+
+
+def _cubic_weights(t: np.ndarray) -> np.ndarray:
+    """Cubic convolution weights (kernel parameter a = -0.75) of the four taps at offsets -1, 0, 1, 2
+    from floor(src), for the fractional position t in [0, 1).  [len(t), 4]."""
+    a = CUBIC_A
+
+    def near(d):    # |d| <= 1
+        return ((a + 2.0) * d - (a + 3.0)) * d * d + 1.0
+
+    def far(d):     # 1 < |d| < 2
+        return ((a * d - 5.0 * a) * d + 8.0 * a) * d - 4.0 * a
+
+    return np.stack([far(t + 1.0), near(t), near(1.0 - t), far(2.0 - t)], axis=-1)
+
+
+def bicubic_upsample(cache_prev, hp: int, wp: int, h: int, w: int) -> np.ndarray:
+    """Separable cubic convolution, half-pixel centres, taps clamped to the grid (edge cells repeat)."""
+    c = _f64(cache_prev)
+    B, _, C = c.shape
+    c = c.reshape(B, hp, wp, C)
+
+    def axis(n_in, n_out):
+        src = (np.arange(n_out) + 0.5) * (n_in / n_out) - 0.5
+        i0 = np.floor(src).astype(np.int64)
+        taps = np.clip(i0[:, None] + np.arange(-1, 3)[None, :], 0, n_in - 1)       # [n_out, 4]
+        return taps, _cubic_weights(src - i0)
+
+    ty, wy = axis(hp, h)
+    tx, wx = axis(wp, w)
+    rows = np.zeros((B, h, wp, C))
+    for j in range(4):
+        rows += c[:, ty[:, j]] * wy[:, j][None, :, None, None]
+    out = np.zeros((B, h, w, C))
+    for j in range(4):
+        out += rows[:, :, tx[:, j]] * wx[:, j][None, None, :, None]
+    return out.reshape(B, h * w, C)
+
+
+UPSAMPLERS = {"bilinear": bilinear_upsample, "nearest": nearest_upsample, "bicubic": bicubic_upsample}
+
+
+def merge_cache(x, y_kept, idx, cache_prev, hp, wp, h, w, interp="bilinear"):
     """Scatter kept outputs back; pruned rows reuse the upsampled residual cache.
+
+    interp: "bilinear" (this build's reading of the interpolation), or the variants "nearest", "bicubic".
 
     out[b, i]       = y_kept[b, s]               if i == idx[b, s]
                     = x[b, i] + cache_up[b, i]   otherwise
@@ -275,7 +334,7 @@ def merge_cache(x, y_kept, idx, cache_prev, hp, wp, h, w):
     assert N == h * w
     k = idx.shape[1]
     if k < N:
-        out = x + bilinear_upsample(cache_prev, hp, wp, h, w)
+        out = x + UPSAMPLERS[interp](cache_prev, hp, wp, h, w)
     else:
         out = np.zeros_like(x)
     for b in range(B):

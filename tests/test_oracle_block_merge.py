@@ -406,3 +406,94 @@ def test_variant_library_second_opinion_torch_float64(use_ada, use_qk, form):
         np.testing.assert_allclose(y[b], ref.numpy(), rtol=1e-9, atol=1e-11)
         np.testing.assert_allclose(kn[b], kh.transpose(0, 1).reshape(-1, C).numpy(), rtol=1e-10, atol=1e-12)
         np.testing.assert_allclose(vn[b], vv.numpy(), rtol=1e-10, atol=1e-12)
+
+
+# ---- other interpolation kernels for the residual cache -------------------------------------
+def test_nearest_upsample_pins():
+    rng = np.random.default_rng(30)
+    c = rng.standard_normal((2, 12, 3))
+    assert np.array_equal(O.nearest_upsample(c, 3, 4, 3, 4), c)                       # same grid: identity
+    # integer factor: every source cell is repeated as a 2 x 3 patch
+    up = O.nearest_upsample(c, 3, 4, 6, 12).reshape(2, 6, 12, 3)
+    src = c.reshape(2, 3, 4, 3)
+    assert np.array_equal(up, np.repeat(np.repeat(src, 2, axis=1), 3, axis=2))
+    # hand case 1 x 3 -> 1 x 5: centres 0.3, 0.9, 1.5, 2.1, 2.7 fall in cells 0, 0, 1, 2, 2
+    row = np.array([10.0, 20.0, 30.0]).reshape(1, 3, 1)
+    assert O.nearest_upsample(row, 1, 3, 1, 5).ravel().tolist() == [10.0, 10.0, 20.0, 30.0, 30.0]
+    # downsampling picks, never mixes
+    down = O.nearest_upsample(c, 3, 4, 2, 2)
+    assert all(any(np.array_equal(v, s) for s in c[0]) for v in down[0])
+
+
+@pytest.mark.parametrize("hp,wp,h,w", [(13, 13, 16, 16), (3, 5, 7, 6), (48, 48, 64, 64), (5, 5, 4, 4), (1, 1, 3, 2)])
+def test_nearest_and_bicubic_library_second_opinion(hp, wp, h, w):
+    rng = np.random.default_rng(31)
+    c = rng.standard_normal((2, hp * wp, 3))
+    t = torch.from_numpy(c).reshape(2, hp, wp, 3).permute(0, 3, 1, 2)
+    back = lambda r: r.permute(0, 2, 3, 1).reshape(2, h * w, 3).numpy()
+    ref_n = F.interpolate(t, size=(h, w), mode="nearest-exact")
+    assert np.array_equal(O.nearest_upsample(c, hp, wp, h, w), back(ref_n))
+    ref_c = F.interpolate(t, size=(h, w), mode="bicubic", align_corners=False, antialias=False)
+    np.testing.assert_allclose(O.bicubic_upsample(c, hp, wp, h, w), back(ref_c), rtol=1e-12, atol=1e-13)
+
+
+def test_bicubic_upsample_closed_forms(monkeypatch):
+    rng = np.random.default_rng(32)
+    c = rng.standard_normal((2, 12, 3))
+    np.testing.assert_allclose(O.bicubic_upsample(c, 3, 4, 3, 4), c, atol=1e-15)       # same grid: weights (0, 1, 0, 0)
+    const = np.full((1, 6, 2), 2.5)
+    np.testing.assert_allclose(O.bicubic_upsample(const, 2, 3, 5, 7), 2.5, rtol=1e-14)  # the weights sum to 1
+    # weights at t = 1/2 with a = -3/4: (-3/32, 19/32, 19/32, -3/32)
+    np.testing.assert_allclose(O._cubic_weights(np.array([0.5]))[0], [-3 / 32, 19 / 32, 19 / 32, -3 / 32], rtol=1e-15)
+    np.testing.assert_allclose(O._cubic_weights(np.linspace(0, 0.999, 50)).sum(axis=-1), 1.0, rtol=1e-14)
+    # 1 x 4 -> 1 x 8: output 3 sits at src 1.25 (taps 0..3, t = 0.25); by hand from the kernel polynomials
+    row = np.array([1.0, -2.0, 4.0, 0.5]).reshape(1, 4, 1)
+    up = O.bicubic_upsample(row, 1, 4, 1, 8).ravel()
+    t = 0.25
+    near = lambda d: (1.25 * d - 2.25) * d * d + 1.0
+    far = lambda d: ((-0.75 * d + 3.75) * d - 6.0) * d + 3.0
+    want = far(1 + t) * 1.0 + near(t) * -2.0 + near(1 - t) * 4.0 + far(2 - t) * 0.5
+    assert up[3] == pytest.approx(want, rel=1e-14)
+    # the first output sits at src -0.25: floor -1, t = 0.75, taps -2..1 clamped to (0, 0, 0, 1)
+    t = 0.75
+    want0 = (far(1 + t) + near(t) + near(1 - t)) * 1.0 + far(2 - t) * -2.0
+    assert up[0] == pytest.approx(want0, rel=1e-14)
+    # the same polynomials with a = -1/2 have a vanishing first moment: linear ramps are then reproduced in
+    # the interior (with a = -3/4 they are not, which the library comparison above covers)
+    monkeypatch.setattr(O, "CUBIC_A", -0.5)
+    hp = wp = 13; h = w = 16
+    yy, xx = np.meshgrid(np.arange(hp), np.arange(wp), indexing="ij")
+    ramp = (2.0 * yy - 3.0 * xx + 1.0).reshape(1, hp * wp, 1)
+    got = O.bicubic_upsample(ramp, hp, wp, h, w).reshape(h, w)
+    sy = (np.arange(h) + 0.5) * hp / h - 0.5
+    inside = (sy >= 1) & (sy <= hp - 2)
+    ref = 2.0 * sy[:, None] - 3.0 * sy[None, :] + 1.0
+    sel = np.ix_(inside, inside)
+    np.testing.assert_allclose(got[sel], ref[sel], rtol=1e-12, atol=1e-12)
+    monkeypatch.setattr(O, "CUBIC_A", -0.75)
+    assert not np.allclose(O.bicubic_upsample(ramp, hp, wp, h, w).reshape(h, w)[sel], ref[sel], atol=1e-3)
+    # transposed field -> transposed result
+    f = rng.standard_normal((5, 7))
+    a = O.bicubic_upsample(f.reshape(1, -1, 1), 5, 7, 8, 9).reshape(8, 9)
+    b = O.bicubic_upsample(f.T.reshape(1, -1, 1), 7, 5, 9, 8).reshape(9, 8)
+    np.testing.assert_allclose(a, b.T, rtol=1e-13, atol=1e-15)
+
+
+@pytest.mark.parametrize("interp", ["nearest", "bicubic"])
+def test_merge_rules_with_other_interpolation(interp):
+    rng = np.random.default_rng(33)
+    B, hp, wp, h, w, C = 2, 3, 3, 4, 4, 5
+    x = rng.standard_normal((B, h * w, C))
+    cache_prev = rng.standard_normal((B, hp * wp, C))
+    idx = np.array([[0, 5, 6, 15], [2, 3, 9, 10]])
+    y = rng.standard_normal((B, 4, C))
+    out, cn = O.merge_cache(x, y, idx, cache_prev, hp, wp, h, w, interp=interp)
+    up = O.UPSAMPLERS[interp](cache_prev, hp, wp, h, w)
+    base, _ = O.merge_cache(x, y, idx, cache_prev, hp, wp, h, w)
+    for b in range(B):
+        kept = idx[b]
+        pruned = np.setdiff1d(np.arange(h * w), kept)
+        assert np.array_equal(out[b, kept], y[b]) and np.array_equal(out[b, kept], base[b, kept])
+        np.testing.assert_allclose(out[b, pruned], x[b, pruned] + up[b, pruned], atol=1e-15)
+        assert not np.allclose(out[b, pruned], base[b, pruned])            # the kernel matters on pruned rows
+    np.testing.assert_allclose(cn, out - x, atol=0)
