@@ -224,6 +224,21 @@ int nova_merge_cache(nova_ctx* ctx, void* stream, int dtype, int B, int C, int h
                      const uint8_t* keep_mask, const void* cache_prev, void* out, void* cache_new);
 
 /*
+ * nova_merge_cache with another interpolation kernel for cache_up (the paper says only that the cache
+ * is interpolated to the next scale's grid; bilinear is this library's default reading):
+ *   NOVA_INTERP_BILINEAR  as nova_merge_cache
+ *   NOVA_INTERP_NEAREST   the source cell containing the output cell's centre:
+ *                         index min(floor((i + 1/2) n_in / n_out), n_in - 1) per axis, exact
+ *   NOVA_INTERP_BICUBIC   separable cubic convolution with kernel parameter a = -3/4, half-pixel
+ *                         centres, taps floor(src) - 1 .. floor(src) + 2 clamped to the grid, fp32
+ * Any other value of `interp` is NOVA_ERR_INVALID_ARG.  Everything else as nova_merge_cache.
+ */
+enum { NOVA_INTERP_BILINEAR = 0, NOVA_INTERP_NEAREST = 1, NOVA_INTERP_BICUBIC = 2 };
+int nova_merge_cache_interp(nova_ctx* ctx, void* stream, int dtype, int interp, int B, int C, int h, int w,
+                            int hp, int wp, int k, const void* x, const void* y_kept, const int32_t* kept_idx,
+                            const uint8_t* keep_mask, const void* cache_prev, void* out, void* cache_new);
+
+/*
  * Ratio controllers (Sec. 3.3, "Adaptive Acceleration Activation" and "Dual-Linkage
  * Acceleration").  The first two are host arithmetic on one instance's scale mean entropies
  * (no GPU work, ctx-free); the third runs on the device so that a layer's keep counts reach

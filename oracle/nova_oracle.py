@@ -266,12 +266,13 @@ def bilinear_upsample(cache_prev, hp: int, wp: int, h: int, w: int) -> np.ndarra
 
 
 def nearest_upsample(cache_prev, hp: int, wp: int, h: int, w: int) -> np.ndarray:
-    """Nearest source cell of each output cell centre: index min(floor((dst + 0.5) n_in / n_out), n_in - 1)."""
+    """Nearest source cell of each output cell centre: index min(floor((dst + 0.5) n_in / n_out), n_in - 1),
+    evaluated in integers ((2 dst + 1) n_in // (2 n_out)) so that centres on a cell boundary are exact."""
     c = _f64(cache_prev)
     B, _, C = c.shape
     c = c.reshape(B, hp, wp, C)
-    iy = np.minimum(np.floor((np.arange(h) + 0.5) * (hp / h)).astype(np.int64), hp - 1)
-    ix = np.minimum(np.floor((np.arange(w) + 0.5) * (wp / w)).astype(np.int64), wp - 1)
+    iy = np.minimum(((2 * np.arange(h, dtype=np.int64) + 1) * hp) // (2 * h), hp - 1)
+    ix = np.minimum(((2 * np.arange(w, dtype=np.int64) + 1) * wp) // (2 * w), wp - 1)
     return c[:, iy][:, :, ix].reshape(B, h * w, C)
 
 

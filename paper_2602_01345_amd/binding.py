@@ -14,6 +14,7 @@ from typing import Dict, Optional, Sequence
 import torch
 
 NOVA_F32, NOVA_BF16 = 0, 1
+NOVA_INTERP_BILINEAR, NOVA_INTERP_NEAREST, NOVA_INTERP_BICUBIC = 0, 1, 2
 STAGES = ("entropy", "select", "gather_ln", "qkv", "attention", "oproj", "ln2", "ffn1", "ffn2", "merge")
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -107,6 +108,8 @@ def load_library() -> C.CDLL:
                                               vp, vp, vp, vp, vp, vp, C.c_size_t]
     lib.nova_pruned_block_variant.restype = i32
     lib.nova_merge_cache.argtypes = [vp, vp, i32] + [i32] * 7 + [vp] * 7
+    lib.nova_merge_cache_interp.argtypes = [vp, vp, i32, i32] + [i32] * 7 + [vp] * 7
+    lib.nova_merge_cache_interp.restype = i32
     lib.nova_profile_stages.argtypes = [vp, C.c_uint32]
     lib.nova_profile_collect.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.nova_activation_scale.argtypes = [C.POINTER(C.c_double), i32, i32, C.c_double, C.POINTER(i32)]
@@ -301,6 +304,17 @@ class Nova:
                                        _ptr(y_kept), _ptr(kept_idx), _ptr(keep_mask), _ptr(cache_prev),
                                        _ptr(out), _ptr(cache_new))
         self._check(rc, "nova_merge_cache")
+
+    def merge_cache_interp(self, interp: int, h: int, w: int, hp: int, wp: int, k: int, x: torch.Tensor,
+                           y_kept: Optional[torch.Tensor], kept_idx: Optional[torch.Tensor],
+                           keep_mask: torch.Tensor, cache_prev: Optional[torch.Tensor], out: torch.Tensor,
+                           cache_new: Optional[torch.Tensor] = None):
+        """interp: NOVA_INTERP_BILINEAR (0), NOVA_INTERP_NEAREST (1), NOVA_INTERP_BICUBIC (2)."""
+        B, _, Cc = x.shape
+        rc = self.lib.nova_merge_cache_interp(self.ctx, _stream(), _dtype_code(x), interp, B, Cc, h, w, hp, wp, k,
+                                              _ptr(x), _ptr(y_kept), _ptr(kept_idx), _ptr(keep_mask),
+                                              _ptr(cache_prev), _ptr(out), _ptr(cache_new))
+        self._check(rc, "nova_merge_cache_interp")
 
 
 # ------------------------------------------------------------------------------------

@@ -295,7 +295,16 @@ int nova_pruned_block_variant(nova_ctx* ctx, void* stream, const nova_block_shap
 int nova_merge_cache(nova_ctx* ctx, void* stream, int dtype, int B, int C, int h, int w, int hp, int wp, int k,
                      const void* x, const void* y_kept, const int32_t* kept_idx, const uint8_t* keep_mask,
                      const void* cache_prev, void* out, void* cache_new) {
+  return nova_merge_cache_interp(ctx, stream, dtype, NOVA_INTERP_BILINEAR, B, C, h, w, hp, wp, k, x, y_kept, kept_idx,
+                                 keep_mask, cache_prev, out, cache_new);
+}
+
+int nova_merge_cache_interp(nova_ctx* ctx, void* stream, int dtype, int interp, int B, int C, int h, int w, int hp,
+                            int wp, int k, const void* x, const void* y_kept, const int32_t* kept_idx,
+                            const uint8_t* keep_mask, const void* cache_prev, void* out, void* cache_new) {
   if (!ctx) return NOVA_ERR_INVALID_ARG;
+  if (interp != NOVA_INTERP_BILINEAR && interp != NOVA_INTERP_NEAREST && interp != NOVA_INTERP_BICUBIC)
+    return NOVA_ERR_INVALID_ARG;
   if (!valid_dtype(dtype)) return NOVA_ERR_UNSUPPORTED;
   if (B < 0 || C < 1 || h < 0 || w < 0 || k < 0) return NOVA_ERR_INVALID_ARG;
   const int64_t N = (int64_t)h * w;
@@ -305,12 +314,13 @@ int nova_merge_cache(nova_ctx* ctx, void* stream, int dtype, int B, int C, int h
   if (!x || !out || !keep_mask || out == x) return NOVA_ERR_INVALID_ARG;
   if (k > 0 && (!y_kept || !kept_idx)) return NOVA_ERR_INVALID_ARG;
   if (k < N && (!cache_prev || hp < 1 || wp < 1)) return NOVA_ERR_INVALID_ARG;
+  if (hp < 1 || wp < 1) cache_prev = nullptr;   // only reachable with k == N: an empty prior grid is never sampled
   const void* ptrs[] = {x, y_kept, cache_prev, out, cache_new};
   for (const void* p : ptrs)
     if (p && !aligned16(p)) return NOVA_ERR_INVALID_ARG;
   if (int rc = set_device(ctx)) return rc;
   StageTimer timer(ctx, static_cast<hipStream_t>(stream), NOVA_STAGE_MERGE);
-  hipError_t e = launch_merge(static_cast<hipStream_t>(stream), dtype, B, C, h, w, hp, wp, k, x, y_kept, kept_idx,
+  hipError_t e = launch_merge(static_cast<hipStream_t>(stream), dtype, interp, B, C, h, w, hp, wp, k, x, y_kept, kept_idx,
                               keep_mask, cache_prev, out, cache_new);
   return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
 }

@@ -5,7 +5,8 @@
 //
 // Bandwidth-bound streaming kernel.  One wave64 owns one token row of C channels and
 // moves it in 16-byte vectors; all loads of a sweep are issued before the first use.
-// The bilinear taps (half-pixel centres) are wave-uniform and evaluated in fp32.
+// The bilinear taps (half-pixel centres) are wave-uniform and evaluated in fp32.  Other interpolation
+// kernels (nearest cell, cubic convolution) go through a generic separable-taps kernel further down.
 #include "common.h"
 #include "nova_internal.h"
 
@@ -138,24 +139,152 @@ __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void merge_kernel(
   }
 }
 
+// ---- other interpolation kernels: NT taps per axis (1 = nearest cell, 4 = cubic convolution) -------------
+template <int NT>
+struct AxisTaps {
+  int i[NT];
+  float w[NT];
+};
+
+// nearest: the source cell that contains the output cell's centre, min(floor((dst + 1/2) n_in / n_out), n_in - 1),
+// in integer arithmetic (centres on a cell boundary must not depend on rounding)
+__device__ __forceinline__ AxisTaps<1> nearest_taps(int dst, int n_in, int n_out) {
+  AxisTaps<1> t;
+  const int64_t q = ((int64_t)(2 * dst + 1) * n_in) / (2 * (int64_t)n_out);
+  t.i[0] = (int)(q > n_in - 1 ? n_in - 1 : q);
+  t.w[0] = 1.0f;
+  return t;
+}
+
+// cubic convolution, kernel parameter a = -3/4, half-pixel centres, taps floor(src) - 1 .. floor(src) + 2
+// clamped to the grid
+__device__ __forceinline__ AxisTaps<4> cubic_taps(int dst, int n_in, int n_out) {
+  constexpr float a = -0.75f;
+  const float src = ((float)dst + 0.5f) * ((float)n_in / (float)n_out) - 0.5f;
+  const float fl = floorf(src);
+  const float t = src - fl;
+  const int i0 = (int)fl;
+  auto near = [](float d) { return ((a + 2.0f) * d - (a + 3.0f)) * d * d + 1.0f; };          // |d| <= 1
+  auto far = [](float d) { return ((a * d - 5.0f * a) * d + 8.0f * a) * d - 4.0f * a; };     // 1 < |d| < 2
+  AxisTaps<4> r;
+  r.w[0] = far(t + 1.0f); r.w[1] = near(t); r.w[2] = near(1.0f - t); r.w[3] = far(2.0f - t);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) r.i[j] = min(max(i0 - 1 + j, 0), n_in - 1);
+  return r;
+}
+
+template <typename T, int NT>
+__global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void merge_taps_kernel(
+    int B, int C, int h, int w, int hp, int wp, int k, const T* __restrict__ x, const T* __restrict__ y,
+    const int32_t* __restrict__ idx, const uint8_t* __restrict__ mask, const T* __restrict__ cache_prev,
+    T* __restrict__ out, T* __restrict__ cache_new) {
+  using VT = Vec16<T>;
+  constexpr int VN = VT::N;
+  const int lane = threadIdx.x & (NOVA_WAVE - 1);
+  const int wave = threadIdx.x / NOVA_WAVE;
+  const int N = h * w;
+  const int64_t row = (int64_t)blockIdx.x * kWavesPerBlock + wave;   // b * N + i
+  if (row >= (int64_t)B * N) return;
+  const int b = (int)(row / N);
+  const int i = (int)(row - (int64_t)b * N);
+  const int nvec = C / VN;
+  const T* xr = x + row * C;
+  T* outr = out + row * C;
+  T* cnr = cache_new ? cache_new + row * C : nullptr;
+
+  if (mask[row] && k > 0) {       // kept token: the block's output, copied; residual = output - input
+    const int32_t* list = idx + (int64_t)b * k;
+    int lo = 0, hi = k - 1;
+    while (lo < hi) {
+      int mid = (lo + hi) >> 1;
+      if (list[mid] < i) lo = mid + 1; else hi = mid;
+    }
+    const T* yr = y + ((int64_t)b * k + lo) * C;
+    for (int vi = lane; vi < nvec; vi += NOVA_WAVE) {
+      VT vy, vx, c;
+      vy.load(yr + vi * VN); vx.load(xr + vi * VN);
+      vy.store(outr + vi * VN);
+      if (cnr) {
+#pragma unroll
+        for (int e = 0; e < VN; ++e) c.set(e, vy.get(e) - vx.get(e));
+        c.store(cnr + vi * VN);
+      }
+    }
+    return;
+  }
+  if (!cache_prev) {              // legal only when every token is kept: pass through, zero residual
+    for (int vi = lane; vi < nvec; vi += NOVA_WAVE) {
+      VT v, z;
+      v.load(xr + vi * VN);
+#pragma unroll
+      for (int e = 0; e < VN; ++e) z.set(e, 0.0f);
+      v.store(outr + vi * VN);
+      if (cnr) z.store(cnr + vi * VN);
+    }
+    return;
+  }
+  const int oy = i / w, ox = i - oy * w;
+  AxisTaps<NT> ty, tx;
+  if constexpr (NT == 1) { ty = nearest_taps(oy, hp, h); tx = nearest_taps(ox, wp, w); }
+  else { ty = cubic_taps(oy, hp, h); tx = cubic_taps(ox, wp, w); }
+  const T* base = cache_prev + (int64_t)b * hp * wp * C;
+  for (int vi = lane; vi < nvec; vi += NOVA_WAVE) {
+    VT vx;
+    vx.load(xr + vi * VN);
+    float up[VN];
+#pragma unroll
+    for (int e = 0; e < VN; ++e) up[e] = 0.0f;
+#pragma unroll
+    for (int jx = 0; jx < NT; ++jx) {
+      float col[VN];                                     // rows first (y), then columns (x)
+#pragma unroll
+      for (int e = 0; e < VN; ++e) col[e] = 0.0f;
+#pragma unroll
+      for (int jy = 0; jy < NT; ++jy) {
+        VT a;
+        a.load(base + ((int64_t)ty.i[jy] * wp + tx.i[jx]) * C + vi * VN);
+#pragma unroll
+        for (int e = 0; e < VN; ++e) col[e] = fmaf(a.get(e), ty.w[jy], col[e]);
+      }
+#pragma unroll
+      for (int e = 0; e < VN; ++e) up[e] = fmaf(col[e], tx.w[jx], up[e]);
+    }
+    VT o, c;
+#pragma unroll
+    for (int e = 0; e < VN; ++e) { o.set(e, vx.get(e) + up[e]); c.set(e, up[e]); }
+    o.store(outr + vi * VN);
+    if (cnr) c.store(cnr + vi * VN);
+  }
+}
+
 template <typename T>
-hipError_t launch_t(hipStream_t st, int B, int C, int h, int w, int hp, int wp, int k, const void* x,
+hipError_t launch_t(hipStream_t st, int interp, int B, int C, int h, int w, int hp, int wp, int k, const void* x,
                     const void* y, const int32_t* idx, const uint8_t* mask, const void* cache_prev, void* out,
                     void* cache_new) {
   const int64_t rows = (int64_t)B * h * w;
   const unsigned grid = (unsigned)((rows + kWavesPerBlock - 1) / kWavesPerBlock);
-  merge_kernel<T><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(
-      B, C, h, w, hp, wp, k, static_cast<const T*>(x), static_cast<const T*>(y), idx, mask,
-      static_cast<const T*>(cache_prev), static_cast<T*>(out), static_cast<T*>(cache_new));
+  const T* xt = static_cast<const T*>(x);
+  const T* yt = static_cast<const T*>(y);
+  const T* ct = static_cast<const T*>(cache_prev);
+  T* ot = static_cast<T*>(out);
+  T* nt = static_cast<T*>(cache_new);
+  if (interp == NOVA_INTERP_NEAREST)
+    merge_taps_kernel<T, 1><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(B, C, h, w, hp, wp, k, xt, yt, idx, mask, ct,
+                                                                       ot, nt);
+  else if (interp == NOVA_INTERP_BICUBIC)
+    merge_taps_kernel<T, 4><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(B, C, h, w, hp, wp, k, xt, yt, idx, mask, ct,
+                                                                       ot, nt);
+  else
+    merge_kernel<T><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(B, C, h, w, hp, wp, k, xt, yt, idx, mask, ct, ot, nt);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_merge(hipStream_t st, int dtype, int B, int C, int h, int w, int hp, int wp, int k,
+hipError_t launch_merge(hipStream_t st, int dtype, int interp, int B, int C, int h, int w, int hp, int wp, int k,
                         const void* x, const void* y, const int32_t* idx, const uint8_t* mask,
                         const void* cache_prev, void* out, void* cache_new) {
   if (dtype == NOVA_BF16)
-    return launch_t<bf16_t>(st, B, C, h, w, hp, wp, k, x, y, idx, mask, cache_prev, out, cache_new);
-  return launch_t<float>(st, B, C, h, w, hp, wp, k, x, y, idx, mask, cache_prev, out, cache_new);
+    return launch_t<bf16_t>(st, interp, B, C, h, w, hp, wp, k, x, y, idx, mask, cache_prev, out, cache_new);
+  return launch_t<float>(st, interp, B, C, h, w, hp, wp, k, x, y, idx, mask, cache_prev, out, cache_new);
 }

@@ -61,7 +61,7 @@ hipError_t launch_entropy_bits(hipStream_t st, const void* logits, int dtype, in
 hipError_t launch_select(hipStream_t st, const float* H, int B, int N, int k, const int32_t* k_per_row,
                          int32_t* idx, uint8_t* mask);
 // merge.hip
-hipError_t launch_merge(hipStream_t st, int dtype, int B, int C, int h, int w, int hp, int wp, int k,
+hipError_t launch_merge(hipStream_t st, int dtype, int interp, int B, int C, int h, int w, int hp, int wp, int k,
                         const void* x, const void* y, const int32_t* idx, const uint8_t* mask,
                         const void* cache_prev, void* out, void* cache_new);
 
