@@ -33,7 +33,7 @@ What each function follows:
                              both norms and gating of both branches by per-image vectors
                              (adaptive LayerNorm conditioning), unit-length queries and keys
                              per head with a per-head score multiplier in place of 1/sqrt(dh),
-                             tanh-form GELU.  The paper names the backbones, not these
+                             tanh-form GELU, a cross-attention sub-layer over condition tokens.  The paper names the backbones, not these
                              details; the formulas are this build's reading (parity unpinned
                              against the paper; pinned to reductions to the base block,
                              invariances and library second opinions).
@@ -170,7 +170,7 @@ def _f64(a):
     return None if a is None else np.asarray(a, dtype=np.float64)
 
 
-def pruned_block(x, idx, weights, k_prior, v_prior, heads, gelu_form="erf", qk_scale=None, ada=None):
+def pruned_block(x, idx, weights, k_prior, v_prior, heads, gelu_form="erf", qk_scale=None, ada=None, cross=None):
     """One transformer block on the kept tokens only.
 
     Variants (all off by default):
@@ -181,6 +181,10 @@ def pruned_block(x, idx, weights, k_prior, v_prior, heads, gelu_form="erf", qk_s
       ada        [B, 6, C] or None: per-image (shift1, scale1, gate1, shift2, scale2, gate2).
                  u = LN(xs) (1 + scale1) + shift1,  x1 = xs + gate1 * attn_branch,
                  FFN input = LN(x1) (1 + scale2) + shift2,  y = x1 + gate2 * ffn_branch.
+      cross      dict or None: a cross-attention sub-layer between the self-attention and the FFN branch,
+                 x1 <- x1 + softmax((LN(x1) w_cq^T + b_cq) Kt^T / sqrt(dh)) Vt w_co^T + b_co per head, with
+                 "k_text", "v_text" [B, Lt, C] the (already projected) keys / values of the condition tokens
+                 and "w_cq", "b_cq", "w_co", "b_co" the query and output projections ([C, C], [C]).
 
     x        [B, N, C]   block input (all tokens of the current scale)
     idx      [B, k]      kept token indices per batch row
@@ -234,6 +238,16 @@ def pruned_block(x, idx, weights, k_prior, v_prior, heads, gelu_form="erf", qk_s
             scores = scores / np.sqrt(dh) if qk_scale is None else scores * qk_scale[h]
             a[:, sl] = softmax(scores) @ Vc[:, sl]
         x1 = xs + gate1 * (a @ W["w_o"].T + bias("b_o"))
+        if cross is not None:
+            Kt, Vt = _f64(cross["k_text"])[b], _f64(cross["v_text"])[b]
+            b_cq = 0.0 if cross.get("b_cq") is None else _f64(cross["b_cq"])
+            b_co = 0.0 if cross.get("b_co") is None else _f64(cross["b_co"])
+            qc = layer_norm(x1) @ _f64(cross["w_cq"]).T + b_cq
+            ac = np.zeros((k, C))
+            for h in range(heads):
+                sl = slice(h * dh, (h + 1) * dh)
+                ac[:, sl] = softmax((qc[:, sl] @ Kt[:, sl].T) / np.sqrt(dh)) @ Vt[:, sl]
+            x1 = x1 + ac @ _f64(cross["w_co"]).T + b_co
         hdn = act((layer_norm(x1) * (1.0 + scale2) + shift2) @ W["w_fc1"].T + bias("b_fc1"))
         y_kept[b] = x1 + gate2 * (hdn @ W["w_fc2"].T + bias("b_fc2"))
     return y_kept, k_new, v_new

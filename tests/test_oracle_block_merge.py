@@ -497,3 +497,80 @@ def test_merge_rules_with_other_interpolation(interp):
         np.testing.assert_allclose(out[b, pruned], x[b, pruned] + up[b, pruned], atol=1e-15)
         assert not np.allclose(out[b, pruned], base[b, pruned])            # the kernel matters on pruned rows
     np.testing.assert_allclose(cn, out - x, atol=0)
+
+
+# ---- cross-attention sub-layer ---------------------------------------------------------------
+def _rand_cross(rng, B, C, Lt, bias=True):
+    return {"w_cq": rng.standard_normal((C, C)) * 0.3, "b_cq": rng.standard_normal(C) * 0.1 if bias else None,
+            "w_co": rng.standard_normal((C, C)) * 0.3, "b_co": rng.standard_normal(C) * 0.1 if bias else None,
+            "k_text": rng.standard_normal((B, Lt, C)), "v_text": rng.standard_normal((B, Lt, C))}
+
+
+def test_cross_attention_reductions():
+    rng = np.random.default_rng(40)
+    x, W, kp, vp = _rand_block(rng, B=2, N=9, P=4)
+    idx = np.array([[0, 1, 4, 8], [2, 3, 5, 6]])
+    base = O.pruned_block(x, idx, W, kp, vp, heads=2)
+    cr = _rand_cross(rng, 2, 8, 5)
+    # a zero output projection switches the sub-layer off; K/V rows appended to the self-attention cache never see it
+    off = dict(cr, w_co=np.zeros((8, 8)), b_co=None)
+    got = O.pruned_block(x, idx, W, kp, vp, heads=2, cross=off)
+    for a, b in zip(got, base):
+        assert np.array_equal(a, b)
+    full = O.pruned_block(x, idx, W, kp, vp, heads=2, cross=cr)
+    assert np.array_equal(full[1], base[1]) and np.array_equal(full[2], base[2])
+    assert not np.allclose(full[0], base[0])
+    # one condition token: every query attends to it alone, so with the FFN output projection zeroed
+    # y = x1 + v_text W_co^T + b_co for every kept row
+    Wz = dict(W, w_fc2=np.zeros_like(W["w_fc2"]), b_fc2=None)
+    one = _rand_cross(rng, 2, 8, 1)
+    y1 = O.pruned_block(x, idx, Wz, kp, vp, heads=2, cross=one)[0]
+    y0 = O.pruned_block(x, idx, Wz, kp, vp, heads=2)[0]
+    for b in range(2):
+        want = one["v_text"][b, 0] @ one["w_co"].T + one["b_co"]
+        np.testing.assert_allclose(y1[b] - y0[b], np.tile(want, (4, 1)), rtol=1e-11, atol=1e-13)
+    # the order of the condition tokens does not matter; image b reads its own tokens only
+    perm = np.array([3, 0, 4, 1, 2])
+    shuffled = dict(cr, k_text=cr["k_text"][:, perm], v_text=cr["v_text"][:, perm])
+    np.testing.assert_allclose(O.pruned_block(x, idx, W, kp, vp, heads=2, cross=shuffled)[0], full[0], rtol=1e-11, atol=1e-13)
+    other = dict(cr, k_text=cr["k_text"].copy(), v_text=cr["v_text"].copy())
+    other["v_text"][1] += 1.0
+    y_other = O.pruned_block(x, idx, W, kp, vp, heads=2, cross=other)[0]
+    assert np.array_equal(y_other[0], full[0][0]) and not np.allclose(y_other[1], full[0][1])
+    # identical keys: uniform attention, the output is the mean value row
+    same = dict(cr, k_text=np.tile(cr["k_text"][:, :1], (1, 5, 1)))
+    ys = O.pruned_block(x, idx, Wz, kp, vp, heads=2, cross=same)[0]
+    for b in range(2):
+        want = same["v_text"][b].mean(axis=0) @ same["w_co"].T + same["b_co"]
+        np.testing.assert_allclose(ys[b] - y0[b], np.tile(want, (4, 1)), rtol=1e-11, atol=1e-13)
+
+
+@pytest.mark.parametrize("bias,with_others", [(True, False), (False, False), (True, True)])
+def test_cross_attention_library_second_opinion_torch_float64(bias, with_others):
+    rng = np.random.default_rng(41)
+    C, heads, dh, Lt = 16, 4, 4, 7
+    x, W, kp, vp = _rand_block(rng, B=2, N=12, C=C, heads=heads, P=5)
+    idx = np.array([[0, 2, 3, 7, 10, 11], [1, 2, 4, 5, 6, 9]])
+    cr = _rand_cross(rng, 2, C, Lt, bias=bias)
+    ada, _ = _rand_variant(rng, 2, C, heads)
+    kw = dict(ada=ada, gelu_form="tanh") if with_others else {}
+    y, kn, vn = O.pruned_block(x, idx, W, kp, vp, heads=heads, cross=cr, **kw)
+    t = {n: torch.from_numpy(a) for n, a in W.items()}
+    c = {n: (None if a is None else torch.from_numpy(a)) for n, a in cr.items()}
+    hd = lambda a: a.reshape(a.shape[0], heads, dh).transpose(0, 1)
+    for b in range(2):
+        m = [torch.from_numpy(v) for v in ada[b]] if with_others else [0.0, 0.0, 1.0, 0.0, 0.0, 1.0]
+        xs = torch.from_numpy(x[b, idx[b]])
+        u = F.layer_norm(xs, (C,), eps=1e-6) * (1.0 + m[1]) + m[0]
+        q, kk, vv = F.linear(u, t["w_qkv"], t["b_qkv"]).split(C, dim=-1)
+        K = torch.cat([torch.from_numpy(kp[b]), kk])
+        V = torch.cat([torch.from_numpy(vp[b]), vv])
+        a = F.scaled_dot_product_attention(hd(q), hd(K), hd(V)).transpose(0, 1).reshape(-1, C)
+        x1 = xs + m[2] * F.linear(a, t["w_o"], t["b_o"])
+        qc = F.linear(F.layer_norm(x1, (C,), eps=1e-6), c["w_cq"], c["b_cq"])
+        ac = F.scaled_dot_product_attention(hd(qc), hd(c["k_text"][b]), hd(c["v_text"][b])).transpose(0, 1).reshape(-1, C)
+        x1 = x1 + F.linear(ac, c["w_co"], c["b_co"])
+        n2 = F.layer_norm(x1, (C,), eps=1e-6) * (1.0 + m[4]) + m[3]
+        hdn = F.gelu(F.linear(n2, t["w_fc1"], t["b_fc1"]), approximate="tanh" if with_others else "none")
+        ref = x1 + m[5] * F.linear(hdn, t["w_fc2"], t["b_fc2"])
+        np.testing.assert_allclose(y[b], ref.numpy(), rtol=1e-9, atol=1e-11)
