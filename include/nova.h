@@ -80,12 +80,29 @@ typedef struct nova_block_weights {
  *              (shift1, scale1, gate1, shift2, scale2, gate2), used as
  *                u  = LN(xs) (1 + scale1) + shift1        x1     = xs + gate1 * (a W_o^T + b_o)
  *                u2 = LN(x1) (1 + scale2) + shift2        y_kept = x1 + gate2 * (GELU(u2 W_fc1^T + b_fc1) W_fc2^T + b_fc2)
+ *   w_cq ...   a cross-attention sub-layer over `text_len` condition tokens, between the self-attention
+ *              branch and the FFN branch (w_cq == NULL: none):
+ *                x1 <- x1 + softmax((LN(x1) w_cq^T + b_cq) Kt^T / sqrt(dh)) Vt w_co^T + b_co   per head
+ *              w_cq, w_co  DEVICE [C, C] out-feature major;  b_cq, b_co  DEVICE [C] or NULL
+ *              k_text      DEVICE [B, heads, text_capacity, dh]  projected keys of the condition tokens,
+ *              v_text      DEVICE [B, heads, dh, text_capacity]  projected values, token index minor
+ *                          (the layouts of k_cache / v_cache); rows / columns [0, text_len) are read
+ *              1 <= text_len <= text_capacity; NOVA_BF16: text_capacity % 64 == 0; NOVA_F32: text_len + dh <= 16384.
+ *              All in the activations' dtype, 16-byte aligned.  Neither qk_norm nor the gates apply to it.
  */
 typedef struct nova_block_variant {
   int32_t gelu_tanh;
   int32_t qk_norm;
   const float* qk_scale;
   const void* ada;
+  const void* w_cq;
+  const void* b_cq;
+  const void* w_co;
+  const void* b_co;
+  const void* k_text;
+  const void* v_text;
+  int32_t text_len;
+  int32_t text_capacity;
 } nova_block_variant;
 
 /* Creates a context for HIP device `device_id` (queries its properties).

@@ -36,7 +36,9 @@ class _Weights(C.Structure):
 
 
 class _Variant(C.Structure):
-    _fields_ = [("gelu_tanh", C.c_int32), ("qk_norm", C.c_int32), ("qk_scale", C.c_void_p), ("ada", C.c_void_p)]
+    _fields_ = [("gelu_tanh", C.c_int32), ("qk_norm", C.c_int32), ("qk_scale", C.c_void_p), ("ada", C.c_void_p),
+                ("w_cq", C.c_void_p), ("b_cq", C.c_void_p), ("w_co", C.c_void_p), ("b_co", C.c_void_p),
+                ("k_text", C.c_void_p), ("v_text", C.c_void_p), ("text_len", C.c_int32), ("text_capacity", C.c_int32)]
 
 
 @dataclass
@@ -46,11 +48,21 @@ class BlockVariant:
     gelu_tanh: bool = False
     qk_scale: Optional[torch.Tensor] = None
     ada: Optional[torch.Tensor] = None
+    # cross-attention sub-layer: "w_cq", "b_cq", "w_co", "b_co" and the condition tokens' projected keys /
+    # values "k_text" [B, heads, capacity, dh], "v_text" [B, heads, dh, capacity] (pack_k_cache / pack_v_cache),
+    # "text_len" (int)
+    cross: Optional[Dict[str, object]] = None
 
     def c_struct(self) -> "_Variant":
         if self.qk_scale is not None:
             assert self.qk_scale.dtype == torch.float32
-        return _Variant(int(self.gelu_tanh), int(self.qk_scale is not None), _ptr(self.qk_scale), _ptr(self.ada))
+        v = _Variant(int(self.gelu_tanh), int(self.qk_scale is not None), _ptr(self.qk_scale), _ptr(self.ada))
+        if self.cross is not None:
+            c = self.cross
+            v.w_cq, v.b_cq, v.w_co, v.b_co = (_ptr(c.get(n)) for n in ("w_cq", "b_cq", "w_co", "b_co"))
+            v.k_text, v.v_text = _ptr(c["k_text"]), _ptr(c["v_text"])
+            v.text_len, v.text_capacity = int(c["text_len"]), int(c["k_text"].shape[2])
+        return v
 
 
 @dataclass

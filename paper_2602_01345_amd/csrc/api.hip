@@ -262,7 +262,7 @@ int nova_pruned_block_variant(nova_ctx* ctx, void* stream, const nova_block_shap
                               const void* x, const int32_t* kept_idx, void* k_cache, void* v_cache, void* y_kept,
                               void* workspace, size_t workspace_bytes) {
   if (!ctx || !weights) return NOVA_ERR_INVALID_ARG;
-  nova_block_variant var = {0, 0, nullptr, nullptr};
+  nova_block_variant var = {};
   if (variant) var = *variant;
   if ((var.gelu_tanh != 0 && var.gelu_tanh != 1) || (var.qk_norm != 0 && var.qk_norm != 1))
     return NOVA_ERR_INVALID_ARG;
@@ -270,6 +270,16 @@ int nova_pruned_block_variant(nova_ctx* ctx, void* stream, const nova_block_shap
     return NOVA_ERR_INVALID_ARG;
   if (var.ada && !aligned16(var.ada)) return NOVA_ERR_INVALID_ARG;
   if (int rc = shape_error(shape)) return rc;
+  if (var.w_cq) {
+    if (!var.w_co || !var.k_text || !var.v_text) return NOVA_ERR_INVALID_ARG;
+    if (var.text_len < 1 || var.text_len > var.text_capacity) return NOVA_ERR_INVALID_ARG;
+    const void* cptrs[] = {var.w_cq, var.b_cq, var.w_co, var.b_co, var.k_text, var.v_text};
+    for (const void* p : cptrs)
+      if (p && !aligned16(p)) return NOVA_ERR_INVALID_ARG;
+    const int dh = shape->C / shape->heads;
+    if (shape->dtype == NOVA_BF16 ? var.text_capacity % 64 != 0 : (int64_t)var.text_len + dh > 16384)
+      return NOVA_ERR_UNSUPPORTED;
+  }
   if (shape->k == 0 || shape->B == 0) return NOVA_OK;
   if (!x || !kept_idx || !k_cache || !v_cache || !y_kept) return NOVA_ERR_INVALID_ARG;
   if (!weights->w_qkv || !weights->w_o || !weights->w_fc1 || !weights->w_fc2) return NOVA_ERR_INVALID_ARG;

@@ -66,6 +66,24 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
     StageTimer t(ctx, st, NOVA_STAGE_OPROJ);
     e = launch_gemm_bf16(ctx, st, EPI_ATTN_OUT, attn, w.w_o, M, C, C, ep);
   }
+  if (e != hipSuccess) return e;
+  if (var.w_cq) {
+    // cross-attention sub-layer over the condition tokens: LN -> query projection -> attention over the
+    // text keys / values -> output projection added to x1 in place (each output element is read and
+    // written by the same thread)
+    e = launch_gather_ln(st, NOVA_BF16, x1, nullptr, M, s.k, s.N, C, nullptr, nullptr, 0, u);
+    if (e != hipSuccess) return e;
+    ep.bias = static_cast<const bf16_t*>(var.b_cq); ep.out = q; ep.ldo = C; ep.gate = nullptr;
+    e = launch_gemm_bf16(ctx, st, EPI_PLAIN, u, var.w_cq, M, C, C, ep);
+    if (e != hipSuccess) return e;
+    e = launch_attention_bf16(ctx, st, q, var.k_text, var.v_text, s.B, s.k, C, s.heads, var.text_capacity,
+                              var.text_len, 1.0f / sqrtf((float)dh), attn, reinterpret_cast<float*>(ws.part_o),
+                              reinterpret_cast<float*>(ws.part_ml));
+    if (e != hipSuccess) return e;
+    ep.bias = static_cast<const bf16_t*>(var.b_co); ep.out = x1; ep.ldo = C; ep.res = x1;
+    e = launch_gemm_bf16(ctx, st, EPI_RESIDUAL, attn, var.w_co, M, C, C, ep);
+    if (e != hipSuccess) return e;
+  }
   {
     StageTimer t(ctx, st, NOVA_STAGE_LN2);
     e = launch_gather_ln(st, NOVA_BF16, x1, nullptr, M, s.k, s.N, C, ada_row(3), ada_row(4), ada_pitch, u);

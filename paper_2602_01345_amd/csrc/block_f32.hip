@@ -131,6 +131,19 @@ hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shap
     StageTimer t(ctx, st, NOVA_STAGE_OPROJ);
     gemm<EPI_ATTN_OUT>(st, attn, static_cast<const float*>(w.w_o), M, C, C, ep);
   }
+  if (var.w_cq) {
+    // cross-attention sub-layer over the condition tokens (see block_bf16.hip)
+    e = launch_gather_ln(st, NOVA_F32, x1, nullptr, M, s.k, s.N, C, nullptr, nullptr, 0, u);
+    if (e != hipSuccess) return e;
+    ep.bias = static_cast<const float*>(var.b_cq); ep.out = q; ep.ldo = C; ep.gate = nullptr;
+    gemm<EPI_PLAIN>(st, u, static_cast<const float*>(var.w_cq), M, C, C, ep);
+    const size_t lds_t = (size_t)(var.text_len + dh) * sizeof(float);
+    attention_f32_kernel<<<dim3(M, s.heads), NOVA_WAVE, lds_t, st>>>(
+        q, static_cast<const float*>(var.k_text), static_cast<const float*>(var.v_text), s.k, C, s.heads, dh,
+        var.text_capacity, var.text_len, 1.0f / sqrtf((float)dh), attn);
+    ep.bias = static_cast<const float*>(var.b_co); ep.out = x1; ep.ldo = C; ep.res = x1;
+    gemm<EPI_RESIDUAL>(st, attn, static_cast<const float*>(var.w_co), M, C, C, ep);
+  }
   {
     StageTimer t(ctx, st, NOVA_STAGE_LN2);
     e = launch_gather_ln(st, NOVA_F32, x1, nullptr, M, s.k, s.N, C, ada_row(3), ada_row(4), ada_pitch, u);

@@ -10,7 +10,8 @@ enum EpiMode {
   EPI_GELU = 2,       // hid = GELU(acc + b_fc1), erf form
   EPI_RESIDUAL = 3,   // y = x1 + acc + b_fc2
   EPI_ENTROPY = 4,    // acc + b are logits: only per-row softmax-entropy partials of the tile's columns leave the kernel
-  EPI_GELU_TANH = 5   // EPI_GELU with the tanh form
+  EPI_GELU_TANH = 5,  // EPI_GELU with the tanh form
+  EPI_PLAIN = 6       // out = acc + b (the query projection of a cross-attention sub-layer)
 };
 
 template <typename T>
@@ -97,6 +98,8 @@ __device__ __forceinline__ void epilogue_store(const EpiParams<T>& p, int row, i
     p.out[(int64_t)row * p.ldo + col] = (T)gelu_erf(v);
   } else if (MODE == EPI_GELU_TANH) {
     p.out[(int64_t)row * p.ldo + col] = (T)gelu_tanh(v);
+  } else if (MODE == EPI_PLAIN) {
+    p.out[(int64_t)row * p.ldo + col] = (T)v;
   } else {
     if (p.gate) v *= (float)p.gate[(int64_t)(row / p.k) * p.gate_pitch + col];
     p.out[(int64_t)row * p.ldo + col] = (T)(v + (float)p.res[(int64_t)row * p.ldo + col]);

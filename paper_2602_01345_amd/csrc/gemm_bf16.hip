@@ -311,7 +311,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
             const int bb = row / ep.k, s = row - bb * ep.k;
             *reinterpret_cast<bf16x8*>(ep.kc + (((int64_t)bb * ep.heads + head) * ep.cap + ep.P + s) * ep.dh + d) = v;
           }
-        } else if (MODE == EPI_GELU || MODE == EPI_GELU_TANH) {
+        } else if (MODE == EPI_GELU || MODE == EPI_GELU_TANH || MODE == EPI_PLAIN) {
           *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + col) = v;
         } else {
           int64_t rrow = row;
@@ -442,6 +442,7 @@ hipError_t launch_gemm_bf16(const nova_ctx* ctx, hipStream_t st, int mode, const
     case EPI_ATTN_OUT: return launch_mode<EPI_ATTN_OUT>(ctx, st, a, w, M, Nout, K, ep);
     case EPI_GELU: return launch_mode<EPI_GELU>(ctx, st, a, w, M, Nout, K, ep);
     case EPI_GELU_TANH: return launch_mode<EPI_GELU_TANH>(ctx, st, a, w, M, Nout, K, ep);
+    case EPI_PLAIN: return launch_mode<EPI_PLAIN>(ctx, st, a, w, M, Nout, K, ep);
     case EPI_ENTROPY: return launch_mode<EPI_ENTROPY>(ctx, st, a, w, M, Nout, K, ep);
     default: return launch_mode<EPI_RESIDUAL>(ctx, st, a, w, M, Nout, K, ep);
   }

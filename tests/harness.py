@@ -58,19 +58,22 @@ class HostBlock:
     k_prior: torch.Tensor
     v_prior: torch.Tensor
     cache_prev: torch.Tensor
-    # block variations: any of "gelu_tanh" (bool), "qk_scale" ([heads] fp32), "ada" ([B, 6, C]); None = base block
+    # block variations: any of "gelu_tanh" (bool), "qk_scale" ([heads] fp32), "ada" ([B, 6, C]), "cross" (dict of
+    # projections and the condition tokens' keys / values [B, Lt, C]); None = base block
     variant: Optional[Dict[str, object]] = None
 
 
 def make_host_block(wl: WL.Workload, j: int, scale: Optional[WL.Scale] = None, k: Optional[int] = None,
-                    variant: Optional[set] = None) -> HostBlock:
-    """`variant`: a subset of {"gelu_tanh", "qk_norm", "ada"} switching block variations on."""
+                    variant: Optional[set] = None, text_len: int = 77) -> HostBlock:
+    """`variant`: a subset of {"gelu_tanh", "qk_norm", "ada", "cross"} switching block variations on."""
     s = scale or wl.last
     kp, vp = WL.make_kv_prior(wl, j, s)
     var = None
     if variant:
-        gen = WL.make_block_variant(wl, j)
+        gen = WL.make_block_variant(wl, j, text_len)
         var = {}
+        if "cross" in variant:
+            var["cross"] = gen["cross"]
         if "gelu_tanh" in variant:
             var["gelu_tanh"] = True
         if "ada" in variant:
@@ -101,9 +104,17 @@ def to_gpu(hb: HostBlock, poison: bool = False):
         cache_prev=hb.cache_prev.to(dev))
     if hb.variant is not None:
         qs, ada = hb.variant.get("qk_scale"), hb.variant.get("ada")
+        cross = hb.variant.get("cross")
+        if cross is not None:
+            Lt = cross["k_text"].shape[1]
+            cap_t = (Lt + 63) // 64 * 64
+            cross = {"w_cq": cross["w_cq"].to(dev), "b_cq": cross["b_cq"].to(dev), "w_co": cross["w_co"].to(dev),
+                     "b_co": cross["b_co"].to(dev), "text_len": Lt,
+                     "k_text": pack_k_cache(cross["k_text"].to(dev), wl.heads, cap_t, fill),
+                     "v_text": pack_v_cache(cross["v_text"].to(dev), wl.heads, cap_t, fill)}
         st.variant = BlockVariant(gelu_tanh=bool(hb.variant.get("gelu_tanh", False)),
                                   qk_scale=None if qs is None else qs.to(dev),
-                                  ada=None if ada is None else ada.to(dev))
+                                  ada=None if ada is None else ada.to(dev), cross=cross)
     runner.add_block(st)
     return runner, st, hb.x.to(dev)
 
@@ -123,6 +134,9 @@ def oracle_block(hb: HostBlock, H32: np.ndarray, rows=None):
             kw["qk_scale"] = f64(hb.variant["qk_scale"])
         if hb.variant.get("ada") is not None:
             kw["ada"] = sel(hb.variant["ada"])
+        if hb.variant.get("cross") is not None:
+            c = hb.variant["cross"]
+            kw["cross"] = {n: (sel(t) if n in ("k_text", "v_text") else f64(t)) for n, t in c.items()}
     y, kn, vn = O.pruned_block(x, idx[:, :hb.k], W, sel(hb.k_prior), sel(hb.v_prior), wl.heads, **kw)
     out, cn = O.merge_cache(x, y, idx[:, :hb.k], sel(hb.cache_prev), s.prev_grid, s.prev_grid, s.grid, s.grid)
     return dict(idx=idx, mask=mask, y=y, k_new=kn, v_new=vn, out=out, cache_new=cn)

@@ -1,5 +1,5 @@
 """GPU parity of the block variants behind nova_pruned_block_variant (per-image modulation and gates,
-unit-length queries/keys with a per-head multiplier, tanh GELU: the ways the backbones of Sec. 4 build
+unit-length queries/keys with a per-head multiplier, tanh GELU, a cross-attention sub-layer: the ways the backbones of Sec. 4 build
 their blocks) against the oracle's statement of the same variants, to the tolerances of the base block."""
 import itertools
 
@@ -11,8 +11,8 @@ import workloads as WL
 
 pytestmark = pytest.mark.gpu
 
-ALL = ("gelu_tanh", "qk_norm", "ada")
-SUBSETS = [set(c) for r in (1, 2, 3) for c in itertools.combinations(ALL, r)]
+ALL = ("gelu_tanh", "qk_norm", "ada", "cross")
+SUBSETS = [set(c) for r in (1, 2, 4) for c in itertools.combinations(ALL, r)]
 
 
 @pytest.fixture(scope="module")
@@ -133,7 +133,7 @@ def test_variant_argument_errors(hx):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("variant", [{"gelu_tanh"}, {"qk_norm"}, {"ada"}], ids=lambda v: "+".join(sorted(v)))
+@pytest.mark.parametrize("variant", [{"gelu_tanh"}, {"qk_norm"}, {"ada"}, {"cross"}], ids=lambda v: "+".join(sorted(v)))
 def test_each_variant_moves_the_output_far_beyond_the_tolerance(hx, dtype, variant):
     """With the benchmark's small weights (std 0.02) both branches are small next to the residual stream, and
     a variant that the device ignored could hide inside the bf16 tolerance.  Here the weights are 8x larger
@@ -143,6 +143,8 @@ def test_each_variant_moves_the_output_far_beyond_the_tolerance(hx, dtype, varia
     wl = _custom(dtype, B=2, grid=12, prev=9, P=70, C=128, heads=2)
     hb = hx.make_host_block(wl, 0, k=90, variant=variant)
     hb.weights = {n: (t * 8.0 if n.startswith("w_") else t) for n, t in hb.weights.items()}
+    if "cross" in variant:
+        hb.variant["cross"] = {n: (t * 8.0 if n.startswith("w_") else t) for n, t in hb.variant["cross"].items()}
     if "gelu_tanh" in variant:
         # the two GELU forms differ by at most 5e-4 in absolute terms: only fp32 can tell them apart
         if dtype == "bf16":
@@ -160,3 +162,47 @@ def test_each_variant_moves_the_output_far_beyond_the_tolerance(hx, dtype, varia
     _say(f"   oracle moves by {moved:.3e} (tolerance {tol:.1e})")
     # the device is many times closer to the oracle with the variant than the oracle without it is
     assert moved > 4 * tol and moved > 20 * errs["y_kept"]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("text_len", [1, 64, 65, 300])
+def test_cross_attention_condition_lengths(hx, dtype, text_len):
+    """One condition token (softmax over a single key), a full tile, a tile plus one, several tiles."""
+    C, heads = (48, 3) if dtype == "f32" else (128, 2)
+    wl = _custom(dtype, B=2, grid=10, prev=7, P=45, C=C, heads=heads)
+    hb = hx.make_host_block(wl, 0, k=37, variant={"cross"}, text_len=text_len)
+    hx.check_block(hb, hx.BF16_TOL if dtype == "bf16" else hx.F32_TOL)
+
+
+def test_cross_attention_argument_errors(hx):
+    from paper_2602_01345_amd import BlockVariant, NovaError
+    wl = _custom("bf16", B=2, grid=9, prev=6, P=64, C=128, heads=2)
+    hb = hx.make_host_block(wl, 0, k=40, variant={"cross"})
+    runner, st, x = hx.to_gpu(hb)
+    good = st.variant
+
+    class Raw(BlockVariant):
+        def __init__(self, edit):
+            self.edit = edit
+
+        def c_struct(self):
+            v = good.c_struct()
+            self.edit(v)
+            return v
+
+    def drop(field):
+        return lambda v: setattr(v, field, None)
+
+    cases = [("no output projection", drop("w_co"), -1), ("no keys", drop("k_text"), -1), ("no values", drop("v_text"), -1),
+             ("zero tokens", lambda v: setattr(v, "text_len", 0), -1),
+             ("more tokens than capacity", lambda v: setattr(v, "text_len", 129), -1),
+             ("misaligned keys", lambda v: setattr(v, "k_text", v.k_text + 2), -1),
+             ("capacity not a multiple of the key tile", lambda v: setattr(v, "text_capacity", 100), -2)]
+    before = st.y_kept.fill_(3.0).clone()
+    for name, edit, code in cases:
+        st.variant = Raw(edit)
+        with pytest.raises(NovaError) as e:
+            runner.run_block(st, x)
+        assert e.value.code == code, name
+    torch.cuda.synchronize()
+    assert torch.equal(st.y_kept, before)

@@ -133,6 +133,7 @@ _TENSOR_IDS = {
     "logits": 1, "temperature": 2, "x": 3, "k_cache": 4, "v_cache": 5, "cache_prev": 6,
     "w_qkv": 10, "b_qkv": 11, "w_o": 12, "b_o": 13, "w_fc1": 14, "b_fc1": 15,
     "w_fc2": 16, "b_fc2": 17, "ada": 20, "qk_scale": 21,
+    "w_cq": 22, "b_cq": 23, "w_co": 24, "b_co": 25, "k_text": 26, "v_text": 27,
 }
 
 
@@ -200,17 +201,25 @@ def make_weights(wl: Workload, block: int) -> Dict[str, torch.Tensor]:
     return {n: _normal(wl.seed, n, block, 0, shp, 0.02, wl.dtype) for n, shp in shapes.items()}
 
 
-def make_block_variant(wl: Workload, block: int) -> Dict[str, torch.Tensor]:
+def make_block_variant(wl: Workload, block: int, text_len: int = 77) -> Dict[str, torch.Tensor]:
     """Inputs of the block variants: per-image conditioning vectors `ada` [B, 6, C] (shift1, scale1,
     gate1, shift2, scale2, gate2; shifts and scales N(0, 0.2^2), gates 1 + N(0, 0.2^2)) in the
-    workload's dtype, and the per-head score multiplier `qk_scale` [heads] fp32, uniform in [4, 16]."""
+    workload's dtype, the per-head score multiplier `qk_scale` [heads] fp32, uniform in [4, 16], and a
+    cross-attention sub-layer: projections N(0, 0.02^2) like the other weights, projected keys / values
+    of `text_len` condition tokens [B, text_len, C], N(0, 1)."""
     g = _rng(wl.seed, "ada", block, 0)
     ada = g.standard_normal(size=(wl.B, 6, wl.C), dtype=np.float32) * np.float32(0.2)
     ada[:, 2] += np.float32(1.0)
     ada[:, 5] += np.float32(1.0)
     gs = _rng(wl.seed, "qk_scale", block, 0)
     qk_scale = gs.uniform(4.0, 16.0, size=(wl.heads,)).astype(np.float32)
-    return {"ada": torch.from_numpy(ada).to(torch_dtype(wl.dtype)), "qk_scale": torch.from_numpy(qk_scale)}
+    C = wl.C
+    cross = {n: _normal(wl.seed, n, block, 0, shp, 0.02, wl.dtype)
+             for n, shp in {"w_cq": (C, C), "b_cq": (C,), "w_co": (C, C), "b_co": (C,)}.items()}
+    cross["k_text"] = _normal(wl.seed, "k_text", block, 0, (wl.B, text_len, C), 1.0, wl.dtype)
+    cross["v_text"] = _normal(wl.seed, "v_text", block, 0, (wl.B, text_len, C), 1.0, wl.dtype)
+    return {"ada": torch.from_numpy(ada).to(torch_dtype(wl.dtype)), "qk_scale": torch.from_numpy(qk_scale),
+            "cross": cross}
 
 
 def small_variant(wl: Workload, B: int | None = None, L: int | None = None) -> Workload:
