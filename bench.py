@@ -182,6 +182,56 @@ def image_chain(nova, wl, weights, gen):
                     "keep table; synthetic inputs"}
 
 
+def variant_step(nova, runner, wl, x, gen, dtype, steps):
+    """The same step with every block variant switched on (inputs drawn on the device; timing only), and the
+    merge kernel of the middle block with each interpolation kernel."""
+    import torch
+    from paper_2602_01345_amd import BlockVariant, pack_k_cache, pack_v_cache
+    Lt, cap_t = 77, 128
+    rnd = lambda shape, std: (torch.randn(shape, generator=gen, device="cuda") * std).to(dtype)
+    res = {"variants": f"modulation+gates, unit-length q/k, tanh GELU, cross-attention over {Lt} condition tokens"}
+
+    def timed_step():
+        for _ in range(2):
+            runner.run_step(x)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            runner.run_step(x)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    res["base_ms_per_step"] = round(timed_step(), 3)
+    for st in runner.blocks:
+        ada = rnd((wl.B, 6, wl.C), 0.2)
+        ada[:, 2] += 1.0
+        ada[:, 5] += 1.0
+        cross = {"w_cq": rnd((wl.C, wl.C), 0.02), "b_cq": rnd((wl.C,), 0.02), "w_co": rnd((wl.C, wl.C), 0.02),
+                 "b_co": rnd((wl.C,), 0.02), "text_len": Lt,
+                 "k_text": pack_k_cache(rnd((wl.B, Lt, wl.C), 1.0), wl.heads, cap_t),
+                 "v_text": pack_v_cache(rnd((wl.B, Lt, wl.C), 1.0), wl.heads, cap_t)}
+        st.variant = BlockVariant(gelu_tanh=True, qk_scale=torch.rand(wl.heads, generator=gen, device="cuda") * 12 + 4,
+                                  ada=ada, cross=cross)
+    res["ms_per_step"] = round(timed_step(), 3)
+    for st in runner.blocks:
+        st.variant = None
+    s, st = wl.last, runner.blocks[len(runner.blocks) // 2]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for interp, name in ((0, "bilinear"), (1, "nearest"), (2, "bicubic")):
+        run = lambda: nova.merge_cache_interp(interp, s.grid, s.grid, s.prev_grid, s.prev_grid, st.k, x, st.y_kept,
+                                              st.kept_idx, st.keep_mask, st.cache_prev, st.out, st.cache_new)
+        for _ in range(5):
+            run()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(20):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        res[f"merge_{name}_us"] = round(e0.elapsed_time(e1) * 1e3 / 20, 2)
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -193,6 +243,10 @@ def main():
     ap.add_argument("--image", action="store_true",
                     help="also time the chained multi-scale run (all scales of the config's grid list) and "
                          "report ms per image")
+    ap.add_argument("--variants", action="store_true",
+                    help="also time the step with the block variants on (modulation and gates, unit-length q/k, "
+                         "tanh GELU, a cross-attention sub-layer over 77 condition tokens) and the other "
+                         "cache interpolation kernels")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (known HBM traffic) for scaling rocprofv3 byte counters")
     args = ap.parse_args()
@@ -405,6 +459,8 @@ def main():
     }
     if args.image:
         out["image_chain"] = image_chain(nova, wl, [st.weights for st in runner.blocks], gen)
+    if args.variants:
+        out["variant_step"] = variant_step(nova, runner, wl, x, gen, dtype, args.steps)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(hb0, wl, scale, ks)
     print(json.dumps(out))

@@ -252,9 +252,103 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
     }
     return;
   }
-  // ---- epilogue, stage 1: accumulators (+ bias, GELU) -> bf16 tile in LDS, row-major --------
   // The MFMAs ran with the weight rows as the A operand, so a lane owns token l % 32 of each MFMA
-  // tile and, per register group r / 4, four consecutive output features: one 8-byte LDS write.
+  // tile and, per register group r / 4, four consecutive output features.
+  if constexpr (MODE != EPI_QKV) {
+    // ---- direct epilogue (everything but the QKV projection): no LDS staging.  A lane owns token l % 32
+    // and, per register group g4, four consecutive features (8 g4 + 4 half ..); swapping the upper lanes'
+    // group g4 with the lower lanes' group g4 + 1 (v_permlane32_swap) leaves every lane with eight
+    // consecutive features of its token: 16-byte residual / gate loads and one 16-byte store, and the two
+    // halves of the wave cover 32 contiguous bytes of each row.
+    constexpr bool HAS_RES = MODE == EPI_ATTN_OUT || MODE == EPI_RESIDUAL;
+    // The residual chunks are requested first, so that their latency (two dependent loads for the
+    // gathered residual) passes behind the conversion work.
+    bf16x8 rs[HAS_RES ? TM * TN * 2 : 1];
+    if constexpr (HAS_RES) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row = m0 + wm * (BM / WM) + i * 32 + r32;
+        int64_t roff = (int64_t)row * ep.ldo;
+        if (MODE == EPI_ATTN_OUT && row < M)
+          roff = ((int64_t)(row / ep.k) * ep.Ntok + min(max(ep.idx[row], 0), ep.Ntok - 1)) * ep.C;
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+          for (int gp = 0; gp < 2; ++gp) {
+            const int col = n0 + wn * (BN / WN) + jn * 32 + 8 * (2 * gp + half);
+            if (row < M && col < Nout) rs[(i * TN + jn) * 2 + gp] = *reinterpret_cast<const bf16x8*>(ep.res + roff + col);
+          }
+      }
+    }
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) {
+      const int cb = n0 + wn * (BN / WN) + jn * 32;                   // first feature of this 32-column block
+      float bias[16];
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int col = cb + 8 * g4 + 4 * half;
+        bf16x4 bv = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
+        if (ep.bias && col < Nout) bv = *reinterpret_cast<const bf16x4*>(ep.bias + col);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bias[g4 * 4 + e] = (float)bv[e];
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row = m0 + wm * (BM / WM) + i * 32 + r32;
+#pragma unroll
+        for (int gp = 0; gp < 2; ++gp) {                              // register groups (2 gp, 2 gp + 1)
+          u32x2 lo, hi;                                               // packed bf16 pairs of the two groups
+#pragma unroll
+          for (int g = 0; g < 2; ++g) {
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              float v = acc[i][jn][(2 * gp + g) * 4 + e] + bias[(2 * gp + g) * 4 + e];
+              if (MODE == EPI_GELU) v = gelu_erf(v);
+              if (MODE == EPI_GELU_TANH) v = gelu_tanh(v);
+              o[e] = (bf16_t)v;
+            }
+            (g == 0 ? lo : hi) = __builtin_bit_cast(u32x2, o);
+          }
+          u32x4 out16;
+#pragma unroll
+          for (int w2 = 0; w2 < 2; ++w2) {
+            const auto sw = __builtin_amdgcn_permlane32_swap(lo[w2], hi[w2], false, false);
+            out16[w2] = sw[0];          // lower lanes: own group 2 gp;       upper lanes: lower partner's group 2 gp + 1
+            out16[2 + w2] = sw[1];      // lower lanes: upper partner's 2 gp; upper lanes: own group 2 gp + 1
+          }
+          const int col = cb + 8 * (2 * gp + half);                   // eight consecutive features from here
+          if (row < M && col < Nout) {
+            if constexpr (HAS_RES) {
+              // the projection (+ bias) is rounded to bf16 before the gate and the residual are applied
+              const bf16x8 v = __builtin_bit_cast(bf16x8, out16);
+              const bf16x8 r = rs[(i * TN + jn) * 2 + gp];
+              bf16x8 o;
+              if (ep.gate) {
+                const bf16x8 gt = *reinterpret_cast<const bf16x8*>(ep.gate + (int64_t)(row / ep.k) * ep.gate_pitch + col);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = (bf16_t)fmaf((float)gt[e], (float)v[e], (float)r[e]);
+              } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = (bf16_t)((float)v[e] + (float)r[e]);
+              }
+              *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + col) = o;
+            } else {
+              *reinterpret_cast<u32x4*>(ep.out + (int64_t)row * ep.ldo + col) = out16;
+            }
+          }
+        }
+      }
+    }
+    return;
+  }
+  // ---- QKV epilogue, stage 1: accumulators (+ bias) -> bf16 tile in LDS, row-major (the value columns are
+  // written transposed, which needs the whole tile at hand) ---------------------------------------------
+  constexpr int NT = NW * 64;
+  constexpr int CPR = BN / 8;                       // chunks per tile row
+  constexpr int RPP = NT / CPR;                     // tile rows covered per pass
+  constexpr int NI = BM / RPP;                      // tile rows per thread
+  static_assert(NT % CPR == 0 && BM % RPP == 0, "chunk walk tiles the output tile");
   bf16_t* ct = reinterpret_cast<bf16_t*>(lds);
 #pragma unroll
   for (int jn = 0; jn < TN; ++jn)
@@ -273,12 +367,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
         const int lrw = wm * (BM / WM) + i * 32 + r32;
         bf16x4 o;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float v = acc[i][jn][g4 * 4 + e] + bias[e];
-          if (MODE == EPI_GELU) v = gelu_erf(v);
-          if (MODE == EPI_GELU_TANH) v = gelu_tanh(v);
-          o[e] = (bf16_t)v;
-        }
+        for (int e = 0; e < 4; ++e) o[e] = (bf16_t)(acc[i][jn][g4 * 4 + e] + bias[e]);
         *reinterpret_cast<bf16x4*>(ct + lrw * CT_PITCH + lc) = o;
       }
     }
@@ -287,51 +376,23 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
   // ---- stage 2: 16-byte row chunks out of LDS, coalesced global stores ----------------------
   // A thread keeps one column chunk and walks down the tile rows, so everything that depends on
   // the column (q / key / value split, head, channel) is computed once.
-  constexpr int NT = NW * 64;
-  constexpr int CPR = BN / 8;                       // chunks per tile row
-  constexpr int RPP = NT / CPR;                     // tile rows covered per pass
-  static_assert(NT % CPR == 0 && BM % RPP == 0, "chunk walk tiles the output tile");
   {
     const int cc = tid % CPR, r_first = tid / CPR;
     const int col = n0 + cc * 8;
-    int sel = 0, cf = col, head = 0, d = 0;
-    if (MODE == EPI_QKV) {
-      sel = col / ep.C; cf = col - sel * ep.C;
-      head = cf / ep.dh; d = cf - head * ep.dh;
-    }
-    if (col < Nout && !(MODE == EPI_QKV && sel == 2)) {
-      for (int lrw = r_first; lrw < BM; lrw += RPP) {
+    const int sel = col / ep.C, cf = col - sel * ep.C;
+    const int head = cf / ep.dh, d = cf - head * ep.dh;
+    if (col < Nout && sel != 2) {
+#pragma unroll
+      for (int it = 0; it < NI; ++it) {
+        const int lrw = r_first + it * RPP;
         const int row = m0 + lrw;
         if (row >= M) break;
         const bf16x8 v = *reinterpret_cast<const bf16x8*>(ct + lrw * CT_PITCH + cc * 8);
-        if (MODE == EPI_QKV) {
-          if (sel == 0) {
-            *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + cf) = v;
-          } else {
-            const int bb = row / ep.k, s = row - bb * ep.k;
-            *reinterpret_cast<bf16x8*>(ep.kc + (((int64_t)bb * ep.heads + head) * ep.cap + ep.P + s) * ep.dh + d) = v;
-          }
-        } else if (MODE == EPI_GELU || MODE == EPI_GELU_TANH || MODE == EPI_PLAIN) {
-          *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + col) = v;
+        if (sel == 0) {
+          *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + cf) = v;
         } else {
-          int64_t rrow = row;
-          int64_t rpitch = ep.ldo;
-          const int bb = row / ep.k;
-          if (MODE == EPI_ATTN_OUT) {
-            rrow = (int64_t)bb * ep.Ntok + min(max(ep.idx[row], 0), ep.Ntok - 1);
-            rpitch = ep.C;
-          }
-          const bf16x8 rs = *reinterpret_cast<const bf16x8*>(ep.res + rrow * rpitch + col);
-          bf16x8 o;
-          if (ep.gate) {
-            const bf16x8 gt = *reinterpret_cast<const bf16x8*>(ep.gate + (int64_t)bb * ep.gate_pitch + col);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (bf16_t)fmaf((float)gt[e], (float)v[e], (float)rs[e]);
-          } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (bf16_t)((float)v[e] + (float)rs[e]);
-          }
-          *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + col) = o;
+          const int bb = row / ep.k, s = row - bb * ep.k;
+          *reinterpret_cast<bf16x8*>(ep.kc + (((int64_t)bb * ep.heads + head) * ep.cap + ep.P + s) * ep.dh + d) = v;
         }
       }
     }
