@@ -53,9 +53,12 @@ BlockWorkspace carve_workspace(const nova_block_shape& s, void* base) {
   w.hid = p + off;  off += up256(M * F * e);
   w.part_o = w.part_ml = nullptr;
   if (s.dtype == NOVA_BF16) {
+    // split-key attention partials: attention_max_split() partial results per item (batch row, head, query
+    // block), each a whole query block (at most 256 queries) of dh floats plus (max, sum) per query
     const size_t ns = (size_t)attention_max_split();
-    w.part_o = p + off;  off += up256(ns * M * C * 4);
-    w.part_ml = p + off; off += up256(ns * M * (size_t)s.heads * 2 * 4);
+    const size_t Mp = (size_t)s.B * (((size_t)s.k + 255) / 256 * 256);
+    w.part_o = p + off;  off += up256(ns * Mp * C * 4);
+    w.part_ml = p + off; off += up256(ns * Mp * (size_t)s.heads * 2 * 4);
   }
   w.total = off;
   return w;

@@ -33,7 +33,7 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 }
 
 constexpr int BKV = 64;              // keys per tile
-constexpr int kMaxSplit = 4;         // most key splits a launch may use (sizes the partial-result workspace)
+constexpr int kMaxSplit = 4;         // sizes the partial-result workspace: kMaxSplit * B * k * C floats
 
 // MFMA row i of a 32-key block reads key pi(i), chosen so that the 8 scores a lane ends up holding
 // in registers 0..7 (and 8..15) belong to 8 consecutive keys: exactly the 8-key run the P^T operand
@@ -53,7 +53,7 @@ __device__ __forceinline__ int swz(int r, int c) {
 template <int DH, int NQ, int NST, int OCC, int NW>
 __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc, int k, int C,
-    int heads, int cap, int kv_total, int nqb, int nsplit, int64_t part_rows, float scale_log2,
+    int heads, int cap, int kv_total, int nqb, int n_whole, int nsplit, float scale_log2,
     bf16_t* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml) {
   constexpr int KROWB = DH * 2;                  // bytes per key row of the K tile
   constexpr int KCH = KROWB / 16;                // chunks per key row
@@ -74,15 +74,22 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int half = lane >> 5, col = lane & 31;
 
-  // ---- workgroup id -> (batch row * heads + head, query block), XCD-contiguous ------------
-  const int nblk = gridDim.x;
-  const int L = blockIdx.x;
-  const int xcd = L & 7, j = L >> 3;
-  const int id = xcd * (nblk >> 3) + min(xcd, nblk & 7) + j;
-  // id -> (batch row * heads + head, query block, key split); the splits of one query block are neighbours
-  const int per_bh = nqb * nsplit;
-  const int bh = id / per_bh, rest = id - bh * per_bh;
-  const int qb = rest / nsplit, split = rest - qb * nsplit;
+  // ---- workgroup id -> item (batch row * heads + head, query block) and key split ---------------
+  // The first n_whole workgroups take one item each over all keys (whole rounds over the CUs); the items
+  // left over for the last, partly filled round are cut into nsplit equal runs of key tiles each, the runs
+  // of an item being neighbours.  Within either group the ids are made XCD-contiguous (the hardware deals
+  // consecutive workgroups to the 8 XCDs in turn), so that the query blocks of one (batch row, head) read
+  // its keys and values through one L2.
+  auto xcd_contiguous = [](int L, int n) {
+    const int xcd = L & 7, j = L >> 3;
+    return xcd * (n >> 3) + min(xcd, n & 7) + j;
+  };
+  const bool whole = (int)blockIdx.x < n_whole;
+  const int pidx = whole ? 0 : xcd_contiguous(blockIdx.x - n_whole, gridDim.x - n_whole);   // index of the partial result
+  const int item = whole ? xcd_contiguous(blockIdx.x, n_whole) : n_whole + pidx / nsplit;
+  const int split = whole ? 0 : pidx % nsplit;
+  const int nparts = whole ? 1 : nsplit;
+  const int bh = item / nqb, qb = item - bh * nqb;
   const int b = bh / heads, head = bh - b * heads;
   const bf16_t* Kg = kc + (int64_t)bh * cap * DH;          // [cap][DH]
   const bf16_t* Vg = vc + (int64_t)bh * DH * (int64_t)cap; // [DH][cap]
@@ -154,7 +161,7 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
 
   // this workgroup's run of key tiles [t_begin, t_end)
   const int ntiles_all = (kv_total + BKV - 1) / BKV;
-  const int tps = (ntiles_all + nsplit - 1) / nsplit;
+  const int tps = (ntiles_all + nparts - 1) / nparts;
   const int t_begin = split * tps;
   const int ntiles = min(ntiles_all, t_begin + tps);       // exclusive end; >= t_begin + 1 (host guarantees)
 #pragma unroll
@@ -290,7 +297,7 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
     const float l_tot = l_run[g] + __shfl_xor(l_run[g], 32, NOVA_WAVE);
     if (qi[g] >= k) continue;
     const int64_t row = (int64_t)b * k + qi[g];
-    if (nsplit == 1) {
+    if (nparts == 1) {
       const float inv = 1.0f / l_tot;
       bf16_t* op = out + row * C + head * DH;
 #pragma unroll
@@ -303,8 +310,10 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
           *reinterpret_cast<bf16x4*>(op + d * 32 + r4 * 8 + half * 4) = v;
         }
     } else {
-      // unnormalised partial sums of this key split, merged by attention_combine_kernel
-      float* po = part_o + ((int64_t)split * part_rows + row) * C + head * DH;
+      // unnormalised partial sums of this key split, [partial][query of the block][DH], merged by
+      // attention_combine_kernel
+      const int64_t prow = (int64_t)pidx * BQ + (qi[g] - qb * BQ);
+      float* po = part_o + prow * DH;
 #pragma unroll
       for (int d = 0; d < DB; ++d)
 #pragma unroll
@@ -315,7 +324,7 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
           *reinterpret_cast<f32x4*>(po + d * 32 + r4 * 8 + half * 4) = v;
         }
       if (half == 0) {
-        float* pm = part_ml + (((int64_t)split * part_rows + row) * heads + head) * 2;
+        float* pm = part_ml + prow * 2;
         pm[0] = m_run[g];
         pm[1] = l_tot;
       }
@@ -323,34 +332,41 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
   }
 }
 
-// Merge of the key splits: out = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^((m_s - max_s m_s) c).
-template <int DH>
-__global__ __launch_bounds__(256) void attention_combine_kernel(const float* __restrict__ part_o,
-                                                                const float* __restrict__ part_ml, int64_t rows,
-                                                                int C, int heads, int nsplit, float scale_log2,
-                                                                bf16_t* __restrict__ out) {
-  const int64_t nvec = rows * (C / 4);
-  for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += (int64_t)gridDim.x * blockDim.x) {
-    const int64_t row = v / (C / 4);
-    const int c = (int)(v - row * (C / 4)) * 4;
-    const int head = c / DH;
-    float mmax = -INFINITY;
-    for (int s = 0; s < nsplit; ++s) mmax = fmaxf(mmax, part_ml[((s * rows + row) * heads + head) * 2]);
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    float l = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
-      const float* pm = part_ml + ((s * rows + row) * heads + head) * 2;
-      const float w = __builtin_amdgcn_exp2f((pm[0] - mmax) * scale_log2);
-      l = fmaf(w, pm[1], l);
-      const f32x4 o = *reinterpret_cast<const f32x4*>(part_o + (s * rows + row) * C + c);
-      acc += w * o;
-    }
-    const float inv = 1.0f / l;
-    bf16x4 r;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) r[e] = (bf16_t)(acc[e] * inv);
-    *reinterpret_cast<bf16x4*>(out + row * C + c) = r;
+// Merge of the key splits of the items that were cut: out = sum_s w_s O_s / sum_s w_s l_s with
+// w_s = 2^((m_s - max_s m_s) c).  The partials of cut item i (counted from n_whole) are [nsplit][BQ][DH] from
+// partial index i * nsplit on.  One thread per 4 output features; a workgroup covers kCombineRows queries
+// of one item.
+constexpr int kCombineRows = 8;
+template <int DH, int BQ>
+__global__ __launch_bounds__(kCombineRows * (DH / 4)) void attention_combine_kernel(
+    const float* __restrict__ part_o, const float* __restrict__ part_ml, int k, int C, int heads, int nqb,
+    int n_whole, int nsplit, float scale_log2, bf16_t* __restrict__ out) {
+  constexpr int CHUNKS = BQ / kCombineRows;                         // workgroups per item
+  const int ci = blockIdx.x / CHUNKS, chunk = blockIdx.x - ci * CHUNKS;
+  const int item = n_whole + ci;
+  const int bh = item / nqb, qb = item - bh * nqb;
+  const int b = bh / heads, head = bh - b * heads;
+  const int qr = chunk * kCombineRows + threadIdx.x / (DH / 4);     // query of the block
+  const int c = (threadIdx.x % (DH / 4)) * 4;
+  const int qrow = qb * BQ + qr;
+  if (qrow >= k) return;
+  const int64_t p0 = (int64_t)ci * nsplit;                          // first partial of this item
+  float mmax = -INFINITY;
+  for (int s = 0; s < nsplit; ++s) mmax = fmaxf(mmax, part_ml[((p0 + s) * BQ + qr) * 2]);
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  float l = 0.f;
+  for (int s = 0; s < nsplit; ++s) {
+    const float* pm = part_ml + ((p0 + s) * BQ + qr) * 2;
+    const float w = __builtin_amdgcn_exp2f((pm[0] - mmax) * scale_log2);
+    l = fmaf(w, pm[1], l);
+    const f32x4 o = *reinterpret_cast<const f32x4*>(part_o + ((p0 + s) * BQ + qr) * DH + c);
+    acc += w * o;
   }
+  const float inv = 1.0f / l;
+  bf16x4 r;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) r[e] = (bf16_t)(acc[e] * inv);
+  *reinterpret_cast<bf16x4*>(out + ((int64_t)b * k + qrow) * C + head * DH + c) = r;
 }
 
 template <int DH, int NQ, int NST, int OCC, int NW>
@@ -359,32 +375,38 @@ hipError_t launch_cfg(const nova_ctx* ctx, hipStream_t st, const bf16_t* q, cons
                       float* part_ml) {
   constexpr int BQ = NW * NQ * 32;
   const int nqb = (k + BQ - 1) / BQ;
-  const int blocks = nqb * heads * B;
-  // Key splits: with few, equally long workgroups the last round over the CUs can be mostly
-  // empty; splitting the key range makes the rounds finer at the price of one small merge pass.
+  const int items = nqb * heads * B;                      // (batch row, head, query block)
   const int slots = (ctx ? ctx->num_cus : 256) * OCC;
   const int ntiles = (kv_total + BKV - 1) / BKV;
-  int nsplit = 1;
+  // Items are equally long, so whole rounds over the CUs are as good as it gets; only the last, partly filled
+  // round is worth cutting: its items are split into nsplit runs of key tiles each (finer rounds), at the price
+  // of partial results for those items and a small merge pass.  The partial workspace holds kMaxSplit * items
+  // partials of BQ * DH floats.
+  int n_whole = items, nsplit = 1;
   if (part_o && part_ml) {
-    float best = 1e30f;
-    // a split count is usable when every split still owns at least one tile
-    auto usable = [&](int s) { return s >= 1 && s <= kMaxSplit && (s - 1) * ((ntiles + s - 1) / s) < ntiles; };
-    for (int s = 1; s <= kMaxSplit; ++s) {
-      if (s > 1 && (ntiles / s < 8 || !usable(s))) break;
-      const float rounds = (float)((blocks * s + slots - 1) / slots);
-      const float cost = rounds / s * (s > 1 ? 1.06f : 1.0f);
-      if (cost < best - 1e-6f) { best = cost; nsplit = s; }
+    const int rest = items % slots;                       // items of the last round (0: nothing to cut)
+    auto usable = [&](int s) {                            // every split owns at least one tile; partials fit
+      return s >= 1 && (s - 1) * ((ntiles + s - 1) / s) < ntiles && (int64_t)rest * s <= (int64_t)kMaxSplit * items;
+    };
+    if (rest > 0) {
+      float best = 1.0f;                                  // time of the last round in units of one item
+      for (int s = 2; s <= 16; ++s) {
+        if (ntiles / s < 8 || !usable(s)) break;
+        const float rounds = (float)(((int64_t)rest * s + slots - 1) / slots);
+        // partial results cost about 5 % of an item per extra split, for the share of the rows that has them
+        const float cost = rounds / s + 0.05f * (s - 1) * (float)rest / (float)items;
+        if (cost < best - 1e-6f) { best = cost; nsplit = s; }
+      }
+      if (ctx && ctx->attn_split >= 1 && usable(ctx->attn_split)) nsplit = ctx->attn_split;
+      if (nsplit > 1) n_whole = items - rest;
     }
-    if (ctx && usable(ctx->attn_split)) nsplit = ctx->attn_split;
   }
-  const int64_t rows = (int64_t)B * k;
-  attention_bf16_kernel<DH, NQ, NST, OCC, NW><<<blocks * nsplit, NW * 64, 0, st>>>(
-      q, kc, vc, k, C, heads, cap, kv_total, nqb, nsplit, rows, scale_log2, out, part_o, part_ml);
-  if (nsplit > 1) {
-    const int64_t nvec = rows * (C / 4);
-    const unsigned grid = (unsigned)std::min<int64_t>((nvec + 255) / 256, 65535);
-    attention_combine_kernel<DH><<<grid, 256, 0, st>>>(part_o, part_ml, rows, C, heads, nsplit, scale_log2, out);
-  }
+  const int grid = n_whole + (items - n_whole) * nsplit;
+  attention_bf16_kernel<DH, NQ, NST, OCC, NW><<<grid, NW * 64, 0, st>>>(
+      q, kc, vc, k, C, heads, cap, kv_total, nqb, n_whole, nsplit, scale_log2, out, part_o, part_ml);
+  if (nsplit > 1)
+    attention_combine_kernel<DH, BQ><<<(items - n_whole) * (BQ / kCombineRows), kCombineRows * (DH / 4), 0, st>>>(
+        part_o, part_ml, k, C, heads, nqb, n_whole, nsplit, scale_log2, out);
   return hipGetLastError();
 }
 

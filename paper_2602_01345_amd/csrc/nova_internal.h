@@ -72,8 +72,8 @@ struct BlockWorkspace {
   char* attn;  // [M, C]  attention output
   char* x1;    // [M, C]  residual stream after attention
   char* hid;   // [M, F]  FFN hidden
-  char* part_o;   // bf16 path: [max_split, M, C] fp32 attention partial sums
-  char* part_ml;  // bf16 path: [max_split, M, heads, 2] fp32 running max / sum
+  char* part_o;   // bf16 path: attention partial sums, fp32: max_split per item, [query block][dh] each
+  char* part_ml;  // bf16 path: their running max / sum per query
   size_t total;
 };
 BlockWorkspace carve_workspace(const nova_block_shape& s, void* base);
@@ -101,8 +101,8 @@ hipError_t launch_head_entropy(const nova_ctx* ctx, hipStream_t st, const void* 
                                const void* b_head, int rows_per_batch, int batch, int C, int V, float* H,
                                float* mean, void* workspace);
 // attention_bf16.hip: attn[B*k, C] = softmax(score_scale * q K^T) V per head over kv_total cached keys
-// part_o / part_ml: workspace for split-key partial results ([max_split, B*k, C] and [max_split, B*k, heads, 2]
-// fp32), or nullptr to forbid splitting
+// part_o / part_ml: workspace for split-key partial results (max_split * B * roundup(k, 256) * C and
+// ... * heads * 2 floats), or nullptr to forbid splitting
 int attention_max_split();
 hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void* q, const void* kc, const void* vc,
                                  int B, int k, int C, int heads, int cap, int kv_total, float score_scale, void* out,
