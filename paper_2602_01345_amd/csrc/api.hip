@@ -86,6 +86,8 @@ int nova_create(nova_ctx** out, int device_id) {
   c->attn_cfg = a ? atoi(a) : -1;
   const char* sp = getenv("NOVA_ATTN_SPLIT");
   c->attn_split = sp ? atoi(sp) : -1;
+  const char* gp = getenv("NOVA_GEMM_PARTS");
+  c->gemm_parts = gp ? atoi(gp) : -1;
   *out = c;
   return NOVA_OK;
 }

@@ -43,7 +43,7 @@ __device__ __forceinline__ int swz(int r, int c) {
 template <int BM, int BN, int WM, int WN, int BK, int NST, bool STAGGER, int MODE>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __restrict__ A,
                                                                 const bf16_t* __restrict__ W, int M, int Nout,
-                                                                int K, int tiles_m, int tiles_n,
+                                                                int K, int m_base, int tiles_m, int tiles_n,
                                                                 EpiParams<bf16_t> ep) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;      // MFMA tiles per wave
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
   const int band = id / (GM * tiles_n), in_band = id - band * (GM * tiles_n);
   const int first_m = band * GM, rows = min(tiles_m - first_m, GM);
   const int tn = in_band / rows, tm = first_m + (in_band - tn * rows);
-  const int m0 = tm * BM, n0 = tn * BN;
+  const int m0 = m_base + tm * BM, n0 = tn * BN;           // this launch covers rows [m_base, M)
 
   // ---- global -> LDS: instruction i of this wave fills tile rows (i * NW + wave) * RPI + lane / CH
   const int lr = lane / CH, lp = lane % CH;
@@ -419,11 +419,11 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
 }
 
 template <int BM, int BN, int WM, int WN, int BK, int NST, bool STAGGER, int MODE>
-hipError_t launch_cfg(hipStream_t st, const bf16_t* A, const bf16_t* W, int M, int Nout, int K,
+hipError_t launch_cfg(hipStream_t st, const bf16_t* A, const bf16_t* W, int m_base, int M, int Nout, int K,
                       const EpiParams<bf16_t>& ep) {
-  const int tiles_m = (M + BM - 1) / BM, tiles_n = (Nout + BN - 1) / BN;
+  const int tiles_m = (M - m_base + BM - 1) / BM, tiles_n = (Nout + BN - 1) / BN;   // rows [m_base, M)
   gemm_bf16_kernel<BM, BN, WM, WN, BK, NST, STAGGER, MODE><<<tiles_m * tiles_n, WM * WN * 64, 0, st>>>(
-      A, W, M, Nout, K, tiles_m, tiles_n, ep);
+      A, W, M, Nout, K, m_base, tiles_m, tiles_n, ep);
   return hipGetLastError();
 }
 
@@ -448,38 +448,89 @@ struct Candidate {
   double rate;   // flop/s of one resident workgroup with all CUs busy
 };
 
-int pick_cfg(const nova_ctx* ctx, int M, int Nout, int K) {
+static const Candidate kCands[] = {{2, 256, 128, 3.3e12}, {5, 128, 128, 3.2e12}, {6, 256, 256, 3.6e12}};
+constexpr double kFixed = 8e-6;          // per round of workgroups: launch ramp, prologue, epilogue
+
+// Modelled time of one launch over M rows with candidate c: whole rounds over the CUs, each a tile's flops at the
+// candidate's sustained rate plus the fixed time.
+double model_time(const Candidate& c, double slots, int M, int Nout, int K) {
+  const double tiles = (double)((M + c.bm - 1) / c.bm) * ((Nout + c.bn - 1) / c.bn);
+  return std::ceil(tiles / slots) * (2.0 * c.bm * c.bn * K / c.rate + kFixed);
+}
+
+int pick_cfg(const nova_ctx* ctx, int M, int Nout, int K, double* t_out = nullptr) {
   if (ctx && ctx->gemm_cfg >= 0 && ctx->gemm_cfg < kNumCfgs) return ctx->gemm_cfg;
   // few rows (the early, small scales): the weights are streamed once and the output has too few
   // large tiles to occupy the CUs, so narrow tiles spread the weight stream over many workgroups
   if (M <= 64) return 3;
   if (M <= 512) return 4;
-  static const Candidate cands[] = {{2, 256, 128, 3.3e12}, {5, 128, 128, 3.2e12}, {6, 256, 256, 3.6e12}};
   const double slots = ctx ? ctx->num_cus : 256;
-  const double t_fixed = 8e-6;
   int best = 2;
   double best_t = 1e30;
-  for (const Candidate& c : cands) {
-    const double tiles = (double)((M + c.bm - 1) / c.bm) * ((Nout + c.bn - 1) / c.bn);
-    const double rounds = std::ceil(tiles / slots);
-    const double t = rounds * (2.0 * c.bm * c.bn * K / c.rate + t_fixed);
+  for (const Candidate& c : kCands) {
+    const double t = model_time(c, slots, M, Nout, K);
     if (t < best_t) { best_t = t; best = c.cfg; }
   }
+  if (t_out) *t_out = best_t;
   return best;
+}
+
+// A launch plan: one configuration for all rows, or two launches -- typically (nearly) whole rounds of large
+// tiles over the first rows and the best single configuration for the rows left over, so that only a small
+// remainder pays for a ragged last round.  Returns the number of parts; part i covers rows [m_base[i], m_end[i]) with cfg[i].
+struct Plan {
+  int n;
+  int m_base[2], m_end[2], cfg[2];
+};
+Plan plan_rows(const nova_ctx* ctx, int mode, int M, int Nout, int K) {
+  Plan p;
+  double t_single = 1e30;
+  p.n = 1; p.m_base[0] = 0; p.m_end[0] = M; p.cfg[0] = pick_cfg(ctx, M, Nout, K, &t_single);
+  const bool forced = ctx && ctx->gemm_cfg >= 0 && ctx->gemm_cfg < kNumCfgs;
+  if (forced || mode == EPI_ENTROPY || M <= 512 || (ctx && ctx->gemm_parts == 0)) return p;
+  const int slots = ctx ? ctx->num_cus : 256;
+  double best = t_single * 0.97;                          // a second launch has to pay for itself
+  for (const Candidate& c : kCands) {
+    for (int rows = 1; rows * c.bm < M; ++rows) {         // tile rows in the first part
+      const int m1 = rows * c.bm;
+      double t_rest = 0.0;
+      const int cfg_rest = pick_cfg(ctx, M - m1, Nout, K, &t_rest);
+      if (M - m1 <= 512) t_rest = model_time(kCands[1], slots, M - m1, Nout, K) * 1.3;   // narrow-tile kernels: slower per flop
+      const double t = model_time(c, slots, m1, Nout, K) + t_rest + 3e-6;
+      if (t < best) {
+        best = t;
+        p.n = 2;
+        p.m_base[0] = 0; p.m_end[0] = m1; p.cfg[0] = c.cfg;
+        p.m_base[1] = m1; p.m_end[1] = M; p.cfg[1] = cfg_rest;
+      }
+    }
+  }
+  return p;
+}
+
+template <int MODE>
+hipError_t launch_part(hipStream_t st, int cfg, const bf16_t* A, const bf16_t* W, int m_base, int M, int Nout, int K,
+                       const EpiParams<bf16_t>& ep) {
+  switch (cfg) {
+    case 0: return launch_cfg<128, 128, 2, 2, 64, 2, false, MODE>(st, A, W, m_base, M, Nout, K, ep);
+    case 1: return launch_cfg<256, 256, 2, 4, 64, 2, false, MODE>(st, A, W, m_base, M, Nout, K, ep);
+    case 3: return launch_cfg<64, 32, 2, 1, 64, 6, true, MODE>(st, A, W, m_base, M, Nout, K, ep);
+    case 4: return launch_cfg<128, 32, 4, 1, 64, 4, true, MODE>(st, A, W, m_base, M, Nout, K, ep);
+    case 5: return launch_cfg<128, 128, 2, 2, 64, 3, false, MODE>(st, A, W, m_base, M, Nout, K, ep);
+    case 6: return launch_cfg<256, 256, 2, 4, 32, 3, false, MODE>(st, A, W, m_base, M, Nout, K, ep);
+    default: return launch_cfg<256, 128, 4, 2, 64, 3, false, MODE>(st, A, W, m_base, M, Nout, K, ep);
+  }
 }
 
 template <int MODE>
 hipError_t launch_mode(const nova_ctx* ctx, hipStream_t st, const bf16_t* A, const bf16_t* W, int M, int Nout,
                        int K, const EpiParams<bf16_t>& ep) {
-  switch (pick_cfg(ctx, M, Nout, K)) {
-    case 0: return launch_cfg<128, 128, 2, 2, 64, 2, false, MODE>(st, A, W, M, Nout, K, ep);
-    case 1: return launch_cfg<256, 256, 2, 4, 64, 2, false, MODE>(st, A, W, M, Nout, K, ep);
-    case 3: return launch_cfg<64, 32, 2, 1, 64, 6, true, MODE>(st, A, W, M, Nout, K, ep);
-    case 4: return launch_cfg<128, 32, 4, 1, 64, 4, true, MODE>(st, A, W, M, Nout, K, ep);
-    case 5: return launch_cfg<128, 128, 2, 2, 64, 3, false, MODE>(st, A, W, M, Nout, K, ep);
-    case 6: return launch_cfg<256, 256, 2, 4, 32, 3, false, MODE>(st, A, W, M, Nout, K, ep);
-    default: return launch_cfg<256, 128, 4, 2, 64, 3, false, MODE>(st, A, W, M, Nout, K, ep);
+  const Plan p = plan_rows(ctx, MODE, M, Nout, K);
+  for (int i = 0; i < p.n; ++i) {
+    const hipError_t e = launch_part<MODE>(st, p.cfg[i], A, W, p.m_base[i], p.m_end[i], Nout, K, ep);
+    if (e != hipSuccess) return e;
   }
+  return hipSuccess;
 }
 
 }  // namespace

@@ -24,6 +24,7 @@ struct nova_ctx {
   int gemm_cfg;   // >= 0 forces one GEMM tile configuration (environment NOVA_GEMM_CFG, for tuning)
   int attn_cfg;   // likewise for the attention kernel (NOVA_ATTN_CFG)
   int attn_split; // >= 1 forces the number of attention key splits (NOVA_ATTN_SPLIT)
+  int gemm_parts; // 0 forbids splitting a GEMM's rows over two launches (NOVA_GEMM_PARTS)
 };
 
 // Brackets one kernel launch with a pair of events when its stage is being timed.
