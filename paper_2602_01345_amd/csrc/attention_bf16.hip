@@ -378,27 +378,45 @@ hipError_t launch_cfg(const nova_ctx* ctx, hipStream_t st, const bf16_t* q, cons
   const int items = nqb * heads * B;                      // (batch row, head, query block)
   const int slots = (ctx ? ctx->num_cus : 256) * OCC;
   const int ntiles = (kv_total + BKV - 1) / BKV;
-  // Items are equally long, so whole rounds over the CUs are as good as it gets; only the last, partly filled
-  // round is worth cutting: its items are split into nsplit runs of key tiles each (finer rounds), at the price
-  // of partial results for those items and a small merge pass.  The partial workspace holds kMaxSplit * items
-  // partials of BQ * DH floats.
+  // Items are equally long, so whole rounds over the workgroup slots run uncut; only the last, partly filled
+  // round is worth cutting into runs of key tiles (finer granularity at the price of partial results for those
+  // items and a small merge pass).  Its time is modelled in units of one item with every slot busy.  Measured:
+  // a workgroup that has its CU to itself runs kSolo times faster, and partial results cost about 5 % of an
+  // item per extra run for the share of the rows that has them.  Three ways to run the last round:
+  //   (i)   uncut;
+  //   (ii)  every item cut into s runs;
+  //   (iii) two resident workgroups per CU only: one uncut item per CU first, the others cut into s runs that
+  //         fill the second slots (and leave the uncut workgroup alone on its CU once they are done).
+  // The partial workspace holds kMaxSplit * items partials of BQ * DH floats.
+  constexpr float kSolo = 1.8f;
   int n_whole = items, nsplit = 1;
   if (part_o && part_ml) {
+    const int cus = slots / OCC;
     const int rest = items % slots;                       // items of the last round (0: nothing to cut)
-    auto usable = [&](int s) {                            // every split owns at least one tile; partials fit
-      return s >= 1 && (s - 1) * ((ntiles + s - 1) / s) < ntiles && (int64_t)rest * s <= (int64_t)kMaxSplit * items;
+    auto usable = [&](int s, int cut) {                   // every run owns at least one tile; partials fit
+      return s >= 1 && (s - 1) * ((ntiles + s - 1) / s) < ntiles && (int64_t)cut * s <= (int64_t)kMaxSplit * items;
     };
     if (rest > 0) {
-      float best = 1.0f;                                  // time of the last round in units of one item
-      for (int s = 2; s <= 16; ++s) {
-        if (ntiles / s < 8 || !usable(s)) break;
-        const float rounds = (float)(((int64_t)rest * s + slots - 1) / slots);
-        // partial results cost about 5 % of an item per extra split, for the share of the rows that has them
-        const float cost = rounds / s + 0.05f * (s - 1) * (float)rest / (float)items;
-        if (cost < best - 1e-6f) { best = cost; nsplit = s; }
+      float best = rest <= cus ? 1.0f / kSolo : 1.0f;     // (i)
+      int best_whole = rest;                              // uncut items of the last round
+      const int forced = ctx && ctx->attn_split >= 2 ? ctx->attn_split : 0;
+      if (forced) best = 1e30f;
+      for (int s = forced ? forced : 2; s <= (forced ? forced : 16); ++s) {
+        if (!forced && ntiles / s < 8) break;
+        if (usable(s, rest)) {                            // (ii)
+          const int pieces = rest * s;
+          const float run = pieces <= cus ? 1.0f / (s * kSolo) : (float)((pieces + slots - 1) / slots) / s;
+          const float cost = run + 0.05f * (s - 1) * (float)rest / (float)items;
+          if (cost < best - 1e-6f) { best = cost; nsplit = s; best_whole = 0; }
+        }
+        if (OCC == 2 && rest > cus && usable(s, rest - cus)) {   // (iii)
+          const float paired = (float)(((rest - cus) * s + cus - 1) / cus) / s;    // second-slot time of the busiest CU
+          const float run = paired <= 1.0f ? paired + (1.0f - paired) / kSolo : 1.0f + (paired - 1.0f) / kSolo;
+          const float cost = run + 0.05f * (s - 1) * (float)(rest - cus) / (float)items;
+          if (cost < best - 1e-6f) { best = cost; nsplit = s; best_whole = cus; }
+        }
       }
-      if (ctx && ctx->attn_split >= 1 && usable(ctx->attn_split)) nsplit = ctx->attn_split;
-      if (nsplit > 1) n_whole = items - rest;
+      if (nsplit > 1) n_whole = items - rest + best_whole;
     }
   }
   const int grid = n_whole + (items - n_whole) * nsplit;

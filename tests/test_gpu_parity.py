@@ -226,6 +226,16 @@ def test_workload_blocks(hx, name, rows, which):
     _say(f"   errors {errs}")
 
 
+def test_cfg5_middle_block_mixed_whole_and_cut_items(hx):
+    """cfg5 block 22 (k = 1348): 352 attention items for 512 workgroup slots, the case in which one uncut item
+    per CU runs next to items cut into key runs."""
+    wl = WL.WORKLOADS["cfg5"]
+    j = 21
+    _say(f"cfg5 block {j} k={wl.k(j)}")
+    errs = hx.check_block(hx.make_host_block(wl, j), hx.BF16_TOL, rows=[0])
+    _say(f"   errors {errs}")
+
+
 def test_earlier_pruned_scales(hx):
     """cfg3's 13x13 scale and cfg5's 32x32 scale (prior grids 10 and 24)."""
     for name, si, rows in (("cfg3", 0, [1]), ("cfg5", 0, [0])):
