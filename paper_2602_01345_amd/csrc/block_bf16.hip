@@ -43,6 +43,7 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
   ep.C = C; ep.heads = s.heads; ep.dh = dh; ep.cap = s.kv_capacity; ep.P = s.kv_len; ep.k = s.k;
   ep.idx = idx; ep.Ntok = s.N;
   ep.gate_pitch = ada_pitch;
+  ep.part = reinterpret_cast<float*>(ws.part_o);          // free once attention is done: K-slice sums of FFN2
 
   ep.bias = static_cast<const bf16_t*>(w.b_qkv); ep.out = q; ep.ldo = C; ep.kc = kc; ep.vc = vc;
   {

@@ -11,7 +11,8 @@ enum EpiMode {
   EPI_RESIDUAL = 3,   // y = x1 + acc + b_fc2
   EPI_ENTROPY = 4,    // acc + b are logits: only per-row softmax-entropy partials of the tile's columns leave the kernel
   EPI_GELU_TANH = 5,  // EPI_GELU with the tanh form
-  EPI_PLAIN = 6       // out = acc + b (the query projection of a cross-attention sub-layer)
+  EPI_PLAIN = 6,      // out = acc + b (the query projection of a cross-attention sub-layer)
+  EPI_PARTIAL = 7     // raw fp32 sums over one slice of K, [slice][M][Nout]; a reduce pass applies the real epilogue
 };
 
 template <typename T>
@@ -33,6 +34,8 @@ struct EpiParams {
   int gate_pitch;
   // EPI_ENTROPY: [column tiles][M] partials (m, S, T, unused) with S = sum e^(x-m), T = sum (m-x) e^(x-m)
   f32x4* ent_part;
+  // K slicing (few rows, long K): fp32 scratch for [slices][M][Nout] partial sums, or nullptr to forbid slicing
+  float* part;
 };
 
 // Exact-form GELU 0.5 v (1 + erf(v / sqrt 2)).  erf through the rational approximation 7.1.26 of

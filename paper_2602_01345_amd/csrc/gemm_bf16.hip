@@ -44,7 +44,7 @@ template <int BM, int BN, int WM, int WN, int BK, int NST, bool STAGGER, int MOD
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __restrict__ A,
                                                                 const bf16_t* __restrict__ W, int M, int Nout,
                                                                 int K, int m_base, int tiles_m, int tiles_n,
-                                                                EpiParams<bf16_t> ep) {
+                                                                int kslices, EpiParams<bf16_t> ep) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;      // MFMA tiles per wave
   constexpr int ROW_BYTES = BK * 2;
@@ -66,8 +66,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
   const int wm = wave / WN, wn = wave % WN;
 
   // ---- workgroup id -> tile, XCD-contiguous, M fastest -------------------------------
+  // kslices > 1 (EPI_PARTIAL only): the grid is kslices copies of the tile grid, copy s sums K slice s
   const int nblk = tiles_m * tiles_n;
-  const int L = blockIdx.x;
+  const int kslice = blockIdx.x / nblk;
+  const int L = blockIdx.x - kslice * nblk;
   const int xcd = L & 7, j = L >> 3;
   const int base = nblk >> 3, rem = nblk & 7;
   const int id = xcd * base + min(xcd, rem) + j;
@@ -117,13 +119,14 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][jn][r] = 0.f;
 
-  const int KT = K / BK;
+  const int KT = K / BK / kslices;                         // K steps of this workgroup's slice
+  const int k_begin = kslice * KT * BK;
   // With few rows every tile column is streamed by one workgroup (or a few that share it), and all
   // of them would walk K in step: the same 128-byte slice of every weight row at the same time,
   // rows a power-of-two stride apart, i.e. a handful of memory channels.  Each tile column
   // therefore starts its (cyclic) walk over K at its own offset.
   const int kt_first = STAGGER ? (int)(((int64_t)tn * KT) / tiles_n) : 0;
-  auto k_of = [&](int t) { const int q = t + kt_first; return (q >= KT ? q - KT : q) * BK; };
+  auto k_of = [&](int t) { const int q = t + kt_first; return k_begin + (q >= KT ? q - KT : q) * BK; };
   // prologue: NST-1 tiles in flight, wait for the first
 #pragma unroll
   for (int t = 0; t < NST - 1; ++t)
@@ -254,7 +257,26 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
   }
   // The MFMAs ran with the weight rows as the A operand, so a lane owns token l % 32 of each MFMA
   // tile and, per register group r / 4, four consecutive output features.
-  if constexpr (MODE != EPI_QKV) {
+  if constexpr (MODE == EPI_PARTIAL) {
+    float* pp = ep.part + (int64_t)kslice * M * Nout;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int row = m0 + wm * (BM / WM) + i * 32 + r32;
+#pragma unroll
+      for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int col = n0 + wn * (BN / WN) + jn * 32 + 8 * g4 + 4 * half;
+          if (row < M && col < Nout) {
+            f32x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = acc[i][jn][g4 * 4 + e];
+            *reinterpret_cast<f32x4*>(pp + (int64_t)row * Nout + col) = v;
+          }
+        }
+    }
+    return;
+  } else if constexpr (MODE != EPI_QKV) {
     // ---- direct epilogue (everything but the QKV projection): no LDS staging.  A lane owns token l % 32
     // and, per register group g4, four consecutive features (8 g4 + 4 half ..); swapping the upper lanes'
     // group g4 with the lower lanes' group g4 + 1 (v_permlane32_swap) leaves every lane with eight
@@ -420,11 +442,44 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
 
 template <int BM, int BN, int WM, int WN, int BK, int NST, bool STAGGER, int MODE>
 hipError_t launch_cfg(hipStream_t st, const bf16_t* A, const bf16_t* W, int m_base, int M, int Nout, int K,
-                      const EpiParams<bf16_t>& ep) {
+                      const EpiParams<bf16_t>& ep, int kslices = 1) {
   const int tiles_m = (M - m_base + BM - 1) / BM, tiles_n = (Nout + BN - 1) / BN;   // rows [m_base, M)
-  gemm_bf16_kernel<BM, BN, WM, WN, BK, NST, STAGGER, MODE><<<tiles_m * tiles_n, WM * WN * 64, 0, st>>>(
-      A, W, M, Nout, K, m_base, tiles_m, tiles_n, ep);
+  gemm_bf16_kernel<BM, BN, WM, WN, BK, NST, STAGGER, MODE><<<tiles_m * tiles_n * kslices, WM * WN * 64, 0, st>>>(
+      A, W, M, Nout, K, m_base, tiles_m, tiles_n, kslices, ep);
   return hipGetLastError();
+}
+
+// Second pass of a K-sliced launch: out = residual-epilogue(sum of the slices + bias) for rows [m_base, M).
+// One thread per 8 output features.
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(const float* __restrict__ part, int kslices, int m_base,
+                                                          int M, int Nout, EpiParams<bf16_t> ep) {
+  const int cpr = Nout / 8;
+  const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (v >= (int64_t)(M - m_base) * cpr) return;
+  const int row = m_base + (int)(v / cpr), col = (int)(v % cpr) * 8;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < kslices; ++s) {
+    const float* p = part + ((int64_t)s * M + row) * Nout + col;
+    const f32x4 a = *reinterpret_cast<const f32x4*>(p), b = *reinterpret_cast<const f32x4*>(p + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { acc[e] += a[e]; acc[4 + e] += b[e]; }
+  }
+  bf16x8 bias;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) bias[e] = (bf16_t)0.f;
+  if (ep.bias) bias = *reinterpret_cast<const bf16x8*>(ep.bias + col);
+  const bf16x8 r = *reinterpret_cast<const bf16x8*>(ep.res + (int64_t)row * ep.ldo + col);
+  bf16x8 o;
+  if (ep.gate) {
+    const bf16x8 gt = *reinterpret_cast<const bf16x8*>(ep.gate + (int64_t)(row / ep.k) * ep.gate_pitch + col);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)      // the projection (+ bias) is rounded to bf16 first, as in the fused epilogue
+      o[e] = (bf16_t)fmaf((float)gt[e], (float)(bf16_t)(acc[e] + (float)bias[e]), (float)r[e]);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (bf16_t)((float)(bf16_t)(acc[e] + (float)bias[e]) + (float)r[e]);
+  }
+  *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + col) = o;
 }
 
 // Tile configurations (NOVA_GEMM_CFG forces one, for tuning):
@@ -495,7 +550,13 @@ Plan plan_rows(const nova_ctx* ctx, int mode, int M, int Nout, int K) {
       const int m1 = rows * c.bm;
       double t_rest = 0.0;
       const int cfg_rest = pick_cfg(ctx, M - m1, Nout, K, &t_rest);
-      if (M - m1 <= 512) t_rest = model_time(kCands[1], slots, M - m1, Nout, K) * 1.3;   // narrow-tile kernels: slower per flop
+      if (M - m1 <= 512) {
+        // the narrow-tile kernels stream the weights once: measured 16 / 21 / 35 us for <= 128 / 256 / 512 rows of
+        // a 2048 x 8192 projection, in proportion to the weight bytes, never under 15 us
+        const int mr = M - m1;
+        const double w_time = 2.0 * Nout * (double)K / 3.2e12 * (mr <= 128 ? 1.0 : mr <= 256 ? 1.45 : 3.0);
+        t_rest = std::max(15e-6, 6e-6 + w_time) + (K >= 4096 ? 5e-6 : 0.0);
+      }
       const double t = model_time(c, slots, m1, Nout, K) + t_rest + 3e-6;
       if (t < best) {
         best = t;
@@ -511,6 +572,22 @@ Plan plan_rows(const nova_ctx* ctx, int mode, int M, int Nout, int K) {
 template <int MODE>
 hipError_t launch_part(hipStream_t st, int cfg, const bf16_t* A, const bf16_t* W, int m_base, int M, int Nout, int K,
                        const EpiParams<bf16_t>& ep) {
+  if constexpr (MODE == EPI_RESIDUAL) {
+    // Few rows and a long K (the FFN down projection of the small scales and of row remainders): a tile column is
+    // one workgroup, too few to stream the weights at speed.  K is cut into slices summed by more workgroups; a
+    // second small pass adds the slices and applies the epilogue.
+    const int wgs = ((M - m_base + (cfg == 3 ? 63 : 127)) / (cfg == 3 ? 64 : 128)) * ((Nout + 31) / 32);
+    if ((cfg == 3 || cfg == 4) && ep.part && wgs <= 128 && K >= 4096 && K % (4 * 64) == 0 && Nout % 8 == 0) {
+      const int ks = 4;
+      const hipError_t e =
+          cfg == 3 ? launch_cfg<64, 32, 2, 1, 64, 6, true, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, ks)
+                   : launch_cfg<128, 32, 4, 1, 64, 4, true, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, ks);
+      if (e != hipSuccess) return e;
+      const int64_t nvec = (int64_t)(M - m_base) * (Nout / 8);
+      gemm_reduce_kernel<<<(unsigned)((nvec + 255) / 256), 256, 0, st>>>(ep.part, ks, m_base, M, Nout, ep);
+      return hipGetLastError();
+    }
+  }
   switch (cfg) {
     case 0: return launch_cfg<128, 128, 2, 2, 64, 2, false, MODE>(st, A, W, m_base, M, Nout, K, ep);
     case 1: return launch_cfg<256, 256, 2, 4, 64, 2, false, MODE>(st, A, W, m_base, M, Nout, K, ep);

@@ -199,6 +199,16 @@ def test_block_f32_small(hx, k):
     _say(f"   errors {errs}")
 
 
+@pytest.mark.parametrize("k", [1, 40, 100])
+def test_block_bf16_few_rows_long_ffn(hx, k):
+    """Few kept rows and an FFN hidden width of 4096: the down projection sums K in slices over several
+    workgroups and a second pass adds the slices (M = 2, 80, 200 rows)."""
+    _say(f"block bf16 C=1024 F=4096 k={k}")
+    wl = _custom("bf16", B=2, grid=10, prev=7, P=64, C=1024, heads=8)
+    errs = hx.check_block(hx.make_host_block(wl, 0, k=k), hx.BF16_TOL)
+    _say(f"   errors {errs}")
+
+
 def test_block_keep_zero_bf16(hx):
     _say("block bf16 k=0")
     wl = _custom("bf16", B=2, grid=8, prev=6, P=64, C=128, heads=2)
