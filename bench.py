@@ -240,6 +240,9 @@ def main():
     ap.add_argument("--config", default="cfg5", help="cfg2..cfg5 (default: the largest, cfg5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stage-pass", action="store_true")
+    ap.add_argument("--overlap", action="store_true",
+                    help="run entropy + selection of the next block on a second stream next to the current block's "
+                         "gather and QKV projection (default: every kernel on one stream)")
     ap.add_argument("--image", action="store_true",
                     help="also time the chained multi-scale run (all scales of the config's grid list) and "
                          "report ms per image")
@@ -295,15 +298,16 @@ def main():
         del src, dst
 
     dom = STAGES.index("attention")
+    overlap = args.overlap
     for _ in range(args.warmup):
-        runner.run_step(x)
+        runner.run_step(x, overlap_selection=overlap)
     torch.cuda.synchronize()
 
     nova.profile_stages([dom])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        runner.run_step(x)
+        runner.run_step(x, overlap_selection=overlap)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     nova.profile_stages([])
@@ -321,7 +325,7 @@ def main():
         nova.profile_stages(range(len(STAGES)))
         reps = max(2, min(args.steps, 5))
         for _ in range(reps):
-            runner.run_step(x)
+            runner.run_step(x, overlap_selection=False)      # one kernel at a time: clean per-kernel durations
         torch.cuda.synchronize()
         nova.profile_stages([])
         for si, name in enumerate(STAGES):
@@ -448,7 +452,8 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: last scale {scale.grid}x{scale.grid}, B={wl.B}, C={wl.C}, heads={wl.heads}, "
                                f"L={wl.L}, V={wl.V}, P={scale.kv_len}, keep {wl.keep_hi}->{wl.keep_lo}",
-                   "kept_tokens_per_step": kept, "blocks": wl.L},
+                   "kept_tokens_per_step": kept, "blocks": wl.L,
+                   "streams": "2 (selection of block j+1 next to the matrix kernels of block j)" if overlap else "1"},
         "roofline": {"kernel": f"attention_bf16_kernel<{wl.dh},...> (+ its split-merge pass)", "bound": "mfma",
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic, "launches": dom_n,

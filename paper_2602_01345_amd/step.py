@@ -43,6 +43,9 @@ class StepRunner:
         self.code = NOVA_BF16 if dtype == torch.bfloat16 else NOVA_F32
         self.blocks: List[BlockState] = []
         self._workspace: Optional[torch.Tensor] = None
+        self._side: Optional[torch.cuda.Stream] = None      # second stream for the look-ahead selection
+        self._selected: List[torch.cuda.Event] = []
+        self._started: List[torch.cuda.Event] = []
 
     def shape(self, k: int) -> BlockShape:
         return BlockShape(self.code, self.B, self.N, self.C, self.heads, self.kv_len, self.kv_capacity, k,
@@ -77,7 +80,50 @@ class StepRunner:
                       st.keep_mask, st.cache_prev, st.out, st.cache_new)
         return st.out
 
-    def run_step(self, x: torch.Tensor) -> torch.Tensor:
-        for st in self.blocks:
-            x = self.run_block(st, x)
+    def _select(self, st: BlockState) -> None:
+        self.nova.entropy(st.logits, st.entropy)
+        self.nova.select(st.entropy, st.k, st.kept_idx, st.keep_mask)
+
+    def _block_and_merge(self, st: BlockState, x: torch.Tensor) -> torch.Tensor:
+        n = self.nova
+        if st.variant is None:
+            n.pruned_block(self.shape(st.k), st.weights, x, st.kept_idx, st.k_cache, st.v_cache, st.y_kept,
+                           self._workspace)
+        else:
+            n.pruned_block_variant(self.shape(st.k), st.weights, st.variant, x, st.kept_idx, st.k_cache,
+                                   st.v_cache, st.y_kept, self._workspace)
+        n.merge_cache(self.grid, self.grid, self.prev_grid, self.prev_grid, st.k, x, st.y_kept, st.kept_idx,
+                      st.keep_mask, st.cache_prev, st.out, st.cache_new)
+        return st.out
+
+    def run_step(self, x: torch.Tensor, overlap_selection: bool = False) -> torch.Tensor:
+        """All blocks of the step.  A block's entropy and selection read only that block's logits (an input of the
+        step), so with overlap_selection they are enqueued one block ahead on a second stream (default priority)
+        and run next to the previous block's gather and QKV projection.  The results are the same launches on the
+        same data either way.  Measured gain on the largest workload: 0.2 % (the entropy kernel fills the CUs, so
+        the two streams mostly take turns); off by default."""
+        if not overlap_selection or len(self.blocks) < 2:
+            for st in self.blocks:
+                x = self.run_block(st, x)
+            return x
+        main = torch.cuda.current_stream()
+        if self._side is None:
+            self._side = torch.cuda.Stream()
+        while len(self._selected) < len(self.blocks):
+            self._selected.append(torch.cuda.Event())
+            self._started.append(torch.cuda.Event())
+        side = self._side
+        self._select(self.blocks[0])
+        for j, st in enumerate(self.blocks):
+            if j + 1 < len(self.blocks):
+                # the look-ahead starts when block j starts (not earlier: the host runs far ahead of the device),
+                # so it lands next to block j's gather and QKV projection
+                self._started[j].record(main)
+                with torch.cuda.stream(side):
+                    side.wait_event(self._started[j])
+                    self._select(self.blocks[j + 1])
+                    self._selected[j + 1].record(side)
+            if j > 0:
+                main.wait_event(self._selected[j])
+            x = self._block_and_merge(st, x)
         return x

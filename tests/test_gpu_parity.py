@@ -319,6 +319,39 @@ def test_block_bf16_forced_key_splits(hx, split, monkeypatch):
     hx.check_block(hb, hx.BF16_TOL)
 
 
+def test_step_with_look_ahead_selection_equals_the_sequential_step(hx):
+    """run_step enqueues every block's entropy + selection one block ahead on a second stream; the outputs must
+    be those of the plain sequence, bit for bit, also when the step is repeated."""
+    wl = WL.Workload("steps", "bf16", B=2, C=128, heads=2, L=4, V=256, keep_hi=.7, keep_lo=.3,
+                     scales=(WL.Scale(grid=12, prev_grid=9, kv_len=130),), seed=11)
+    runner = None
+    for j in range(wl.L):
+        r, st, x = hx.to_gpu(hx.make_host_block(wl, j))
+        if runner is None:
+            runner = r
+        else:
+            runner.add_block(st)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for st in runner.blocks for t in (st.entropy, st.kept_idx, st.keep_mask, st.out, st.cache_new)]
+
+    def poison():
+        for st in runner.blocks:
+            st.out.fill_(float("nan"))
+            st.entropy.fill_(-1.0)
+            st.kept_idx.fill_(-7)
+            st.keep_mask.fill_(9)
+
+    runner.run_step(x, overlap_selection=False)
+    ref = snapshot()
+    for rep in range(3):
+        poison()
+        runner.run_step(x, overlap_selection=True)
+        got = snapshot()
+        assert all(torch.equal(a, b) for a, b in zip(ref, got)), f"repeat {rep}"
+
+
 def test_block_is_deterministic(hx):
     """Two runs on the same inputs give the same bits (no atomics on the block / merge path)."""
     wl = _custom("bf16", B=2, grid=24, prev=18, P=900, C=256, heads=4)
