@@ -173,10 +173,13 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
 
   // A-operand row of this lane inside a 32-key block (see key_of_mfma_row)
   const int krow = key_of_mfma_row(col);
-  int stage = 0, fill = NST - 1;
-  // One 64-key tile.  TAIL (last tile only) masks the scores of keys past kv_total.
-  auto tile_body = [&](auto tail_tag, int t) {
+  // One 64-key tile.  TAIL (last tile only) masks the scores of keys past kv_total.  stage_v is the ring stage
+  // the tile sits in: a compile-time constant with a two-stage ring (the tile loop is unrolled by two, so that
+  // every LDS address is a per-lane offset plus an immediate), a run-time value otherwise.
+  auto tile_body = [&](auto tail_tag, auto stage_v, int t) {
     constexpr bool TAIL = decltype(tail_tag)::value;
+    const int stage = stage_v;
+    const int fill = stage == 0 ? NST - 1 : stage - 1;    // the stage freed by the previous tile
     const int key0 = t * BKV;
     const bool more = t + NST - 1 < ntiles;
     if (more) issue(fill, (t + NST - 1) * BKV);
@@ -286,11 +289,29 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
-    stage = stage + 1 == NST ? 0 : stage + 1;
-    fill = fill + 1 == NST ? 0 : fill + 1;
   };
-  for (int t = t_begin; t + 1 < ntiles; ++t) tile_body(std::false_type{}, t);
-  tile_body(std::true_type{}, ntiles - 1);
+  if constexpr (NST == 2) {
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+    int t = t_begin;
+    for (; t + 2 < ntiles; t += 2) {
+      tile_body(std::false_type{}, S0{}, t);
+      tile_body(std::false_type{}, S1{}, t + 1);
+    }
+    if (t + 2 == ntiles) {
+      tile_body(std::false_type{}, S0{}, t);
+      tile_body(std::true_type{}, S1{}, t + 1);
+    } else {
+      tile_body(std::true_type{}, S0{}, t);
+    }
+  } else {
+    int stage = 0;
+    for (int t = t_begin; t + 1 < ntiles; ++t) {
+      tile_body(std::false_type{}, stage, t);
+      stage = stage + 1 == NST ? 0 : stage + 1;
+    }
+    tile_body(std::true_type{}, stage, ntiles - 1);
+  }
 
 #pragma unroll
   for (int g = 0; g < NQ; ++g) {
