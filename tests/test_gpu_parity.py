@@ -236,11 +236,13 @@ def test_workload_blocks(hx, name, rows, which):
     _say(f"   errors {errs}")
 
 
-def test_cfg5_middle_block_mixed_whole_and_cut_items(hx):
+@pytest.mark.parametrize("j", [21, 27])
+def test_cfg5_middle_blocks_ragged_last_rounds(hx, j):
     """cfg5 block 22 (k = 1348): 352 attention items for 512 workgroup slots, the case in which one uncut item
-    per CU runs next to items cut into key runs."""
+    per CU runs next to items cut into key runs.  Block 28 (k = 1031, 2062 rows): the projections cover 2048 rows
+    with one whole round of large tiles and the last 14 rows with the narrow-tile kernels (K-sliced for the FFN
+    down projection)."""
     wl = WL.WORKLOADS["cfg5"]
-    j = 21
     _say(f"cfg5 block {j} k={wl.k(j)}")
     errs = hx.check_block(hx.make_host_block(wl, j), hx.BF16_TOL, rows=[0])
     _say(f"   errors {errs}")
