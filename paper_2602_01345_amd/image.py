@@ -24,7 +24,7 @@ from typing import Dict, List, Optional, Sequence
 
 import torch
 
-from .binding import NOVA_BF16, NOVA_F32, BlockShape, Nova
+from .binding import NOVA_BF16, NOVA_F32, BlockShape, BlockVariant, Nova
 
 
 @dataclass
@@ -61,8 +61,13 @@ class ScalePlan:
 
 class ImageRunner:
     def __init__(self, nova: Nova, *, B: int, C: int, heads: int, grids: Sequence[int], dtype: torch.dtype,
-                 weights: List[Dict[str, torch.Tensor]], ffn_mult: int = 4, device: str = "cuda"):
+                 weights: List[Dict[str, torch.Tensor]], ffn_mult: int = 4, device: str = "cuda",
+                 variants: Optional[List[Optional[BlockVariant]]] = None, interp: int = 0):
+        """variants: per block, the block variations (nova_pruned_block_variant) or None; interp: the cache
+        interpolation kernel of nova_merge_cache_interp (0 bilinear, 1 nearest, 2 bicubic)."""
         self.nova = nova
+        self.variants = variants if variants is not None else [None] * len(weights)
+        self.interp = interp
         self.B, self.C, self.heads, self.ffn_mult = B, C, heads, ffn_mult
         self.grids = list(grids)
         self.dtype = dtype
@@ -151,10 +156,10 @@ class ImageRunner:
                 n.entropy(plan.logits[j], plan.entropy)
                 n.select(plan.entropy, k, plan.idx[j], plan.mask[j])
             shape = BlockShape(self.code, self.B, N, self.C, self.heads, plan.kv_len[j], self.cap, k, self.ffn_mult)
-            n.pruned_block(shape, self.weights[j], x, plan.idx[j], self.k_cache[j], self.v_cache[j], plan.y[j],
-                           self._workspace)
-            n.merge_cache(g, g, plan.prev_grid, plan.prev_grid, k, x, plan.y[j], plan.idx[j], plan.mask[j],
-                          plan.cache_prev[j], plan.out[j], plan.cache_new[j])
+            n.pruned_block_variant(shape, self.weights[j], self.variants[j], x, plan.idx[j], self.k_cache[j],
+                                   self.v_cache[j], plan.y[j], self._workspace)
+            n.merge_cache_interp(self.interp, g, g, plan.prev_grid, plan.prev_grid, k, x, plan.y[j], plan.idx[j],
+                                 plan.mask[j], plan.cache_prev[j], plan.out[j], plan.cache_new[j])
             x = plan.out[j]
         return x
 
@@ -224,9 +229,10 @@ class ImageRunner:
             y = torch.empty((B, max(k, 1), C), dtype=self.dtype, device=dev)
             out = torch.empty((B, N, C), dtype=self.dtype, device=dev)
             cache_new = torch.empty((B, N, C), dtype=self.dtype, device=dev) if keep_cache else None
-            n.pruned_block(shape, self.weights[j], x, idx, self.k_cache[j], self.v_cache[j], y, self._workspace)
+            n.pruned_block_variant(shape, self.weights[j], self.variants[j], x, idx, self.k_cache[j], self.v_cache[j],
+                                   y, self._workspace)
             pg = self.cache_grid if self.cache[j] is not None else g
-            n.merge_cache(g, g, pg, pg, k, x, y, idx, mask, self.cache[j], out, cache_new)
+            n.merge_cache_interp(self.interp, g, g, pg, pg, k, x, y, idx, mask, self.cache[j], out, cache_new)
             self.kv_len[j] += k
             if inspect:
                 ents.append(H.clone())

@@ -30,13 +30,22 @@ def _workload(dtype, B, C, heads, L, V, grids):
                        scales=scales, seed=3)
 
 
-def _run_chain(dtype, B, C, heads, L, V, grids, first_pruned, tol, controller):
+def _run_chain(dtype, B, C, heads, L, V, grids, first_pruned, tol, controller, variants=False, interp="bilinear"):
     wl = _workload(dtype, B, C, heads, L, V, grids)
     tdt = WL.torch_dtype(dtype)
     weights_h = [WL.make_weights(wl, j) for j in range(L)]
     weights_d = [{n: t.cuda() for n, t in w.items()} for w in weights_h]
     W64 = [{n: Hn.f64(t) for n, t in w.items()} for w in weights_h]
-    runner = ImageRunner(Hn.nova(), B=B, C=C, heads=heads, grids=grids, dtype=tdt, weights=weights_d)
+    var_d, var_kw = None, [{} for _ in range(L)]
+    if variants:
+        # modulation + gates, unit-length q/k and tanh GELU in every block (the key cache then holds unit-length
+        # keys from the first scale on, as both sides append them)
+        from paper_2602_01345_amd import BlockVariant
+        gen = [WL.make_block_variant(wl, j) for j in range(L)]
+        var_d = [BlockVariant(gelu_tanh=True, qk_scale=g["qk_scale"].cuda(), ada=g["ada"].cuda()) for g in gen]
+        var_kw = [dict(gelu_form="tanh", qk_scale=Hn.f64(g["qk_scale"]), ada=Hn.f64(g["ada"])) for g in gen]
+    runner = ImageRunner(Hn.nova(), B=B, C=C, heads=heads, grids=grids, dtype=tdt, weights=weights_d,
+                         variants=var_d, interp={"bilinear": 0, "nearest": 1, "bicubic": 2}[interp])
 
     k_prior = [np.zeros((B, 0, C)) for _ in range(L)]
     v_prior = [np.zeros((B, 0, C)) for _ in range(L)]
@@ -79,12 +88,12 @@ def _run_chain(dtype, B, C, heads, L, V, grids, first_pruned, tol, controller):
                 assert np.array_equal(res.block_idx[j].cpu().numpy(), idx), (t, j)
             else:
                 idx = np.tile(np.arange(N), (B, 1))
-            y, kn, vn = O.pruned_block(x, idx, W64[j], k_prior[j], v_prior[j], heads)
+            y, kn, vn = O.pruned_block(x, idx, W64[j], k_prior[j], v_prior[j], heads, **var_kw[j])
             if cache[j] is None:
                 assert k == N
                 out, cn = O.merge_cache(x, y, idx, np.zeros((B, N, C)), g, g, g, g)
             else:
-                out, cn = O.merge_cache(x, y, idx, cache[j], cache_grid, cache_grid, g, g)
+                out, cn = O.merge_cache(x, y, idx, cache[j], cache_grid, cache_grid, g, g, interp=interp)
             out, cn, kn, vn = (_store(a, tdt) for a in (out, cn, kn, vn))
             # compare what the device produced and stored
             e_out = Hn.nerr(res.block_out[j], out)
@@ -122,6 +131,19 @@ def test_chain_bf16(controller):
     # matrix-core path: dh = 64, several key tiles and a ragged tail at every scale
     _run_chain("bf16", B=2, C=128, heads=2, L=3, V=256, grids=[3, 5, 8, 11, 13], first_pruned=2,
                tol=Hn.BF16_TOL * 1.5, controller=controller)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype,interp", [("f32", "bicubic"), ("bf16", "nearest"), ("bf16", "bicubic")])
+def test_chain_with_block_variants_and_other_interpolation(dtype, interp):
+    """The chained run with every block built the other way (modulation and gates, unit-length q/k, tanh GELU)
+    and the residual cache interpolated with another kernel."""
+    if dtype == "f32":
+        _run_chain("f32", B=2, C=64, heads=2, L=2, V=128, grids=[2, 3, 4, 6, 8], first_pruned=2,
+                   tol=Hn.F32_TOL * 4, controller=False, variants=True, interp=interp)
+    else:
+        _run_chain("bf16", B=2, C=128, heads=2, L=3, V=256, grids=[3, 5, 8, 11, 13], first_pruned=2,
+                   tol=Hn.BF16_TOL * 1.5, controller=False, variants=True, interp=interp)
 
 
 @pytest.mark.gpu
