@@ -507,13 +507,19 @@ static const Candidate kCands[] = {{2, 256, 128, 3.3e12}, {5, 128, 128, 3.2e12},
 constexpr double kFixed = 8e-6;          // per round of workgroups: launch ramp, prologue, epilogue
 
 // Modelled time of one launch over M rows with candidate c: whole rounds over the CUs, each a tile's flops at the
-// candidate's sustained rate plus the fixed time.
-double model_time(const Candidate& c, double slots, int M, int Nout, int K) {
+// candidate's sustained rate plus the fixed time.  A projection done by one launch of a single round that fills
+// only a fraction f of the CUs is shorter (the busy CUs share L2 and memory with fewer others): taken as
+// max(0.85, 1.1 f) of a whole round (`alone`).  Measured over the 32 blocks of the largest workload this helps the
+// K = 2048 projections; for the parts of a two-launch plan and for K = 8192 it misleads and is not applied.
+double model_time(const Candidate& c, double slots, int M, int Nout, int K, bool alone = false) {
   const double tiles = (double)((M + c.bm - 1) / c.bm) * ((Nout + c.bn - 1) / c.bn);
-  return std::ceil(tiles / slots) * (2.0 * c.bm * c.bn * K / c.rate + kFixed);
+  const double t_tile = 2.0 * c.bm * c.bn * K / c.rate;
+  if (alone && K < 4096 && tiles < slots)   // a whole projection that fills only a fraction of the CUs
+    return t_tile * std::max(0.85, std::min(1.0, 1.1 * tiles / slots)) + kFixed;
+  return std::ceil(tiles / slots) * (t_tile + kFixed);
 }
 
-int pick_cfg(const nova_ctx* ctx, int M, int Nout, int K, double* t_out = nullptr) {
+int pick_cfg(const nova_ctx* ctx, int M, int Nout, int K, double* t_out = nullptr, bool alone = true) {
   if (ctx && ctx->gemm_cfg >= 0 && ctx->gemm_cfg < kNumCfgs) return ctx->gemm_cfg;
   // few rows (the early, small scales): the weights are streamed once and the output has too few
   // large tiles to occupy the CUs, so narrow tiles spread the weight stream over many workgroups
@@ -523,7 +529,7 @@ int pick_cfg(const nova_ctx* ctx, int M, int Nout, int K, double* t_out = nullpt
   int best = 2;
   double best_t = 1e30;
   for (const Candidate& c : kCands) {
-    const double t = model_time(c, slots, M, Nout, K);
+    const double t = model_time(c, slots, M, Nout, K, alone);
     if (t < best_t) { best_t = t; best = c.cfg; }
   }
   if (t_out) *t_out = best_t;
@@ -549,7 +555,7 @@ Plan plan_rows(const nova_ctx* ctx, int mode, int M, int Nout, int K) {
     for (int rows = 1; rows * c.bm < M; ++rows) {         // tile rows in the first part
       const int m1 = rows * c.bm;
       double t_rest = 0.0;
-      const int cfg_rest = pick_cfg(ctx, M - m1, Nout, K, &t_rest);
+      const int cfg_rest = pick_cfg(ctx, M - m1, Nout, K, &t_rest, false);
       if (M - m1 <= 512) {
         // the narrow-tile kernels stream the weights once: measured 16 / 21 / 35 us for <= 128 / 256 / 512 rows of
         // a 2048 x 8192 projection, in proportion to the weight bytes, never under 15 us
