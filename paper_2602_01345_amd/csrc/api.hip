@@ -88,6 +88,8 @@ int nova_create(nova_ctx** out, int device_id) {
   c->attn_split = sp ? atoi(sp) : -1;
   const char* gp = getenv("NOVA_GEMM_PARTS");
   c->gemm_parts = gp ? atoi(gp) : -1;
+  const char* gs = getenv("NOVA_GEMM_PERSIST");
+  c->gemm_persist = gs ? atoi(gs) : -1;
   *out = c;
   return NOVA_OK;
 }

@@ -40,6 +40,15 @@ __device__ __forceinline__ int swz(int r, int c) {
   return r * 64 + ((c ^ ((r >> 2) & 3)) << 4);
 }
 
+// Whether a workgroup walks several tiles (one workgroup per CU): the modes whose epilogue needs no LDS, large
+// tiles only; with a residual the prefetched residual chunks of a wave's MFMA tiles must leave room in the
+// register file for the next tile's addresses (at most 4 MFMA tiles per wave).
+constexpr bool persistent_tiles(int mfma_tiles_per_wave, bool stagger, int mode) {
+  if (stagger) return false;
+  if (mode == EPI_GELU || mode == EPI_GELU_TANH || mode == EPI_PLAIN) return true;
+  return (mode == EPI_ATTN_OUT || mode == EPI_RESIDUAL) && mfma_tiles_per_wave <= 4;
+}
+
 template <int BM, int BN, int WM, int WN, int BK, int NST, bool STAGGER, int MODE>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __restrict__ A,
                                                                 const bf16_t* __restrict__ W, int M, int Nout,
@@ -67,36 +76,47 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
 
   // ---- workgroup id -> tile, XCD-contiguous, M fastest -------------------------------
   // kslices > 1 (EPI_PARTIAL only): the grid is kslices copies of the tile grid, copy s sums K slice s
+  // PERSIST (the modes whose epilogue needs no LDS, large tiles): the grid is one workgroup per CU and a
+  // workgroup takes the tiles L, L + gridDim.x, ...; the first K stages of its next tile are requested
+  // before the epilogue of the current one, so their latency passes behind the epilogue.
+  constexpr bool PERSIST = persistent_tiles(BM / WM / 32 * (BN / WN / 32), STAGGER, MODE);
   const int nblk = tiles_m * tiles_n;
-  const int kslice = blockIdx.x / nblk;
-  const int L = blockIdx.x - kslice * nblk;
-  const int xcd = L & 7, j = L >> 3;
-  const int base = nblk >> 3, rem = nblk & 7;
-  const int id = xcd * base + min(xcd, rem) + j;
-  // bands of GM tile rows, column by column inside a band: the workgroups an XCD runs at the same
-  // time then cover a compact GM x (slots / GM) rectangle and share A and W tiles in its L2
-  constexpr int GM = 8;
-  const int band = id / (GM * tiles_n), in_band = id - band * (GM * tiles_n);
-  const int first_m = band * GM, rows = min(tiles_m - first_m, GM);
-  const int tn = in_band / rows, tm = first_m + (in_band - tn * rows);
-  const int m0 = m_base + tm * BM, n0 = tn * BN;           // this launch covers rows [m_base, M)
-
+  const int kslice = PERSIST ? 0 : blockIdx.x / nblk;
+  int L = blockIdx.x - kslice * nblk;
   // ---- global -> LDS: instruction i of this wave fills tile rows (i * NW + wave) * RPI + lane / CH
   const int lr = lane / CH, lp = lane % CH;
   const bf16_t* ga[LA];
   const bf16_t* gb[LB];
+  int tn = 0, m0 = 0, n0 = 0;
+  auto set_tile = [&](int Lt) {
+    // Lt -> tile, XCD-contiguous (gridDim.x is a multiple of 8 when a workgroup takes several tiles, so all of
+    // them have its XCD's residue)
+    const int xcd = Lt & 7, j = Lt >> 3;
+    const int base = nblk >> 3, rem = nblk & 7;
+    const int id = xcd * base + min(xcd, rem) + j;
+    // bands of GM tile rows, column by column inside a band: the workgroups an XCD runs at the same
+    // time then cover a compact GM x (slots / GM) rectangle and share A and W tiles in its L2
+    constexpr int GM = 8;
+    const int band = id / (GM * tiles_n), in_band = id - band * (GM * tiles_n);
+    const int first_m = band * GM, rows = min(tiles_m - first_m, GM);
+    tn = in_band / rows;
+    const int tm = first_m + (in_band - tn * rows);
+    m0 = m_base + tm * BM;                                 // this launch covers rows [m_base, M)
+    n0 = tn * BN;
 #pragma unroll
-  for (int i = 0; i < LA; ++i) {
-    const int r = (i * NW + wave) * RPI + lr;
-    const int c = (swz<BK>(r, lp) - r * ROW_BYTES) >> 4;   // chunk of the row that lands in slot lp
-    ga[i] = A + (int64_t)min(m0 + r, M - 1) * K + c * 8;   // rows past the edge re-read the last row
-  }
+    for (int i = 0; i < LA; ++i) {
+      const int r = (i * NW + wave) * RPI + lr;
+      const int c = (swz<BK>(r, lp) - r * ROW_BYTES) >> 4;   // chunk of the row that lands in slot lp
+      ga[i] = A + (int64_t)min(m0 + r, M - 1) * K + c * 8;   // rows past the edge re-read the last row
+    }
 #pragma unroll
-  for (int i = 0; i < LB; ++i) {
-    const int r = (i * NW + wave) * RPI + lr;
-    const int c = (swz<BK>(r, lp) - r * ROW_BYTES) >> 4;
-    gb[i] = W + (int64_t)min(n0 + r, Nout - 1) * K + c * 8;
-  }
+    for (int i = 0; i < LB; ++i) {
+      const int r = (i * NW + wave) * RPI + lr;
+      const int c = (swz<BK>(r, lp) - r * ROW_BYTES) >> 4;
+      gb[i] = W + (int64_t)min(n0 + r, Nout - 1) * K + c * 8;
+    }
+  };
+  set_tile(L);
   // load instructions lo..hi-1 (A first, then W) of the tile at K offset k0 into `stage`
   auto issue = [&](int stage, int k0, int lo, int hi) {
     char* sa = lds + stage * STAGE;
@@ -112,12 +132,6 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
   };
 
   f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int jn = 0; jn < TN; ++jn)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][jn][r] = 0.f;
 
   const int KT = K / BK / kslices;                         // K steps of this workgroup's slice
   const int k_begin = kslice * KT * BK;
@@ -127,12 +141,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
   // therefore starts its (cyclic) walk over K at its own offset.
   const int kt_first = STAGGER ? (int)(((int64_t)tn * KT) / tiles_n) : 0;
   auto k_of = [&](int t) { const int q = t + kt_first; return k_begin + (q >= KT ? q - KT : q) * BK; };
-  // prologue: NST-1 tiles in flight, wait for the first
+  // prologue: NST-1 K stages in flight
+  auto prologue = [&]() {
 #pragma unroll
-  for (int t = 0; t < NST - 1; ++t)
-    if (t < KT) issue(t, k_of(t), 0, LPW);
-  if (KT >= NST - 1) { WAIT_VMCNT((NST - 2) * LPW); } else { WAIT_VMCNT(0); }
-  __syncthreads();
+    for (int t = 0; t < NST - 1; ++t)
+      if (t < KT) issue(t, k_of(t), 0, LPW);
+  };
+  prologue();
 
   const int half = lane >> 5, r32 = lane & 31;
   const int arow0 = wm * (BM / WM) + r32;   // tile row of this lane's A operand in MFMA tile 0
@@ -166,6 +181,19 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
   constexpr int LEAD = 1;                   // MFMAs issued before the next K step's LDS reads
   static_assert(KS % 2 == 0, "fragment buffers alternate per K step");
 
+  bool first_tile = true;
+  for (;;) {   // tiles of this workgroup (one, unless PERSIST)
+  // wait for the first K stage.  After a prefetch the epilogue's own loads and stores are in flight as well and
+  // the counter does not tell them apart: wait for everything.
+  if (first_tile && KT >= NST - 1) { WAIT_VMCNT((NST - 2) * LPW); } else { WAIT_VMCNT(0); }
+  first_tile = false;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][jn][r] = 0.f;
   int stage = 0, fill = NST - 1;            // stage being computed / stage being refilled
   read_frags(0, 0, 0);
   for (int kt = 0; kt < KT; ++kt) {
@@ -277,6 +305,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
     }
     return;
   } else if constexpr (MODE != EPI_QKV) {
+    const int em0 = m0, en0 = n0;            // origin of the tile whose accumulators are written out below
     // ---- direct epilogue (everything but the QKV projection): no LDS staging.  A lane owns token l % 32
     // and, per register group g4, four consecutive features (8 g4 + 4 half ..); swapping the upper lanes'
     // group g4 with the lower lanes' group g4 + 1 (v_permlane32_swap) leaves every lane with eight
@@ -289,7 +318,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
     if constexpr (HAS_RES) {
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
-        const int row = m0 + wm * (BM / WM) + i * 32 + r32;
+        const int row = em0 + wm * (BM / WM) + i * 32 + r32;
         int64_t roff = (int64_t)row * ep.ldo;
         if (MODE == EPI_ATTN_OUT && row < M)
           roff = ((int64_t)(row / ep.k) * ep.Ntok + min(max(ep.idx[row], 0), ep.Ntok - 1)) * ep.C;
@@ -297,26 +326,44 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
         for (int jn = 0; jn < TN; ++jn)
 #pragma unroll
           for (int gp = 0; gp < 2; ++gp) {
-            const int col = n0 + wn * (BN / WN) + jn * 32 + 8 * (2 * gp + half);
+            const int col = en0 + wn * (BN / WN) + jn * 32 + 8 * (2 * gp + half);
             if (row < M && col < Nout) rs[(i * TN + jn) * 2 + gp] = *reinterpret_cast<const bf16x8*>(ep.res + roff + col);
           }
       }
     }
+    bf16x4 bvec[TN][4];                       // this lane's bias entries, packed
 #pragma unroll
-    for (int jn = 0; jn < TN; ++jn) {
-      const int cb = n0 + wn * (BN / WN) + jn * 32;                   // first feature of this 32-column block
-      float bias[16];
+    for (int jn = 0; jn < TN; ++jn)
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
-        const int col = cb + 8 * g4 + 4 * half;
+        const int col = en0 + wn * (BN / WN) + jn * 32 + 8 * g4 + 4 * half;
         bf16x4 bv = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
         if (ep.bias && col < Nout) bv = *reinterpret_cast<const bf16x4*>(ep.bias + col);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) bias[g4 * 4 + e] = (float)bv[e];
+        bvec[jn][g4] = bv;
       }
+    bool more_tiles = false;
+    if constexpr (PERSIST) {
+      // Every wave has passed the last barrier of the K loop, nobody reads the ring any more: request the
+      // first stages of this workgroup's next tile now.  They are requested after the epilogue's own loads
+      // (loads complete in order, so those do not wait for the tile data) and land behind the conversion work.
+      if (L + (int)gridDim.x < nblk) {
+        more_tiles = true;
+        L += gridDim.x;
+        set_tile(L);
+        prologue();
+      }
+    }
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) {
+      const int cb = en0 + wn * (BN / WN) + jn * 32;                   // first feature of this 32-column block
+      float bias[16];
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bias[g4 * 4 + e] = (float)bvec[jn][g4][e];
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
-        const int row = m0 + wm * (BM / WM) + i * 32 + r32;
+        const int row = em0 + wm * (BM / WM) + i * 32 + r32;
 #pragma unroll
         for (int gp = 0; gp < 2; ++gp) {                              // register groups (2 gp, 2 gp + 1)
           u32x2 lo, hi;                                               // packed bf16 pairs of the two groups
@@ -362,7 +409,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
         }
       }
     }
+    if (more_tiles) continue;
     return;
+  }
+  break;   // the QKV projection: staged epilogue below
   }
   // ---- QKV epilogue, stage 1: accumulators (+ bias) -> bf16 tile in LDS, row-major (the value columns are
   // written transposed, which needs the whole tile at hand) ---------------------------------------------
@@ -442,9 +492,14 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
 
 template <int BM, int BN, int WM, int WN, int BK, int NST, bool STAGGER, int MODE>
 hipError_t launch_cfg(hipStream_t st, const bf16_t* A, const bf16_t* W, int m_base, int M, int Nout, int K,
-                      const EpiParams<bf16_t>& ep, int kslices = 1) {
+                      const EpiParams<bf16_t>& ep, int slots, int kslices = 1) {
   const int tiles_m = (M - m_base + BM - 1) / BM, tiles_n = (Nout + BN - 1) / BN;   // rows [m_base, M)
-  gemm_bf16_kernel<BM, BN, WM, WN, BK, NST, STAGGER, MODE><<<tiles_m * tiles_n * kslices, WM * WN * 64, 0, st>>>(
+  // the kernel's PERSIST modes walk several tiles per workgroup: one workgroup per CU then (a multiple of 8, so
+  // that a workgroup's tiles share its XCD)
+  constexpr bool PERSIST = persistent_tiles(BM / WM / 32 * (BN / WN / 32), STAGGER, MODE);
+  int grid = tiles_m * tiles_n * kslices;
+  if (PERSIST && slots > 0 && slots % 8 == 0 && grid > slots) grid = slots;
+  gemm_bf16_kernel<BM, BN, WM, WN, BK, NST, STAGGER, MODE><<<grid, WM * WN * 64, 0, st>>>(
       A, W, M, Nout, K, m_base, tiles_m, tiles_n, kslices, ep);
   return hipGetLastError();
 }
@@ -577,7 +632,7 @@ Plan plan_rows(const nova_ctx* ctx, int mode, int M, int Nout, int K) {
 
 template <int MODE>
 hipError_t launch_part(hipStream_t st, int cfg, const bf16_t* A, const bf16_t* W, int m_base, int M, int Nout, int K,
-                       const EpiParams<bf16_t>& ep) {
+                       const EpiParams<bf16_t>& ep, int slots) {
   if constexpr (MODE == EPI_RESIDUAL) {
     // Few rows and a long K (the FFN down projection of the small scales and of row remainders): a tile column is
     // one workgroup, too few to stream the weights at speed.  K is cut into slices summed by more workgroups; a
@@ -586,8 +641,8 @@ hipError_t launch_part(hipStream_t st, int cfg, const bf16_t* A, const bf16_t* W
     if ((cfg == 3 || cfg == 4) && ep.part && wgs <= 128 && K >= 4096 && K % (4 * 64) == 0 && Nout % 8 == 0) {
       const int ks = 4;
       const hipError_t e =
-          cfg == 3 ? launch_cfg<64, 32, 2, 1, 64, 6, true, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, ks)
-                   : launch_cfg<128, 32, 4, 1, 64, 4, true, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, ks);
+          cfg == 3 ? launch_cfg<64, 32, 2, 1, 64, 6, true, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, 0, ks)
+                   : launch_cfg<128, 32, 4, 1, 64, 4, true, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, 0, ks);
       if (e != hipSuccess) return e;
       const int64_t nvec = (int64_t)(M - m_base) * (Nout / 8);
       gemm_reduce_kernel<<<(unsigned)((nvec + 255) / 256), 256, 0, st>>>(ep.part, ks, m_base, M, Nout, ep);
@@ -595,13 +650,13 @@ hipError_t launch_part(hipStream_t st, int cfg, const bf16_t* A, const bf16_t* W
     }
   }
   switch (cfg) {
-    case 0: return launch_cfg<128, 128, 2, 2, 64, 2, false, MODE>(st, A, W, m_base, M, Nout, K, ep);
-    case 1: return launch_cfg<256, 256, 2, 4, 64, 2, false, MODE>(st, A, W, m_base, M, Nout, K, ep);
-    case 3: return launch_cfg<64, 32, 2, 1, 64, 6, true, MODE>(st, A, W, m_base, M, Nout, K, ep);
-    case 4: return launch_cfg<128, 32, 4, 1, 64, 4, true, MODE>(st, A, W, m_base, M, Nout, K, ep);
-    case 5: return launch_cfg<128, 128, 2, 2, 64, 3, false, MODE>(st, A, W, m_base, M, Nout, K, ep);
-    case 6: return launch_cfg<256, 256, 2, 4, 32, 3, false, MODE>(st, A, W, m_base, M, Nout, K, ep);
-    default: return launch_cfg<256, 128, 4, 2, 64, 3, false, MODE>(st, A, W, m_base, M, Nout, K, ep);
+    case 0: return launch_cfg<128, 128, 2, 2, 64, 2, false, MODE>(st, A, W, m_base, M, Nout, K, ep, slots);
+    case 1: return launch_cfg<256, 256, 2, 4, 64, 2, false, MODE>(st, A, W, m_base, M, Nout, K, ep, slots);
+    case 3: return launch_cfg<64, 32, 2, 1, 64, 6, true, MODE>(st, A, W, m_base, M, Nout, K, ep, slots);
+    case 4: return launch_cfg<128, 32, 4, 1, 64, 4, true, MODE>(st, A, W, m_base, M, Nout, K, ep, slots);
+    case 5: return launch_cfg<128, 128, 2, 2, 64, 3, false, MODE>(st, A, W, m_base, M, Nout, K, ep, slots);
+    case 6: return launch_cfg<256, 256, 2, 4, 32, 3, false, MODE>(st, A, W, m_base, M, Nout, K, ep, slots);
+    default: return launch_cfg<256, 128, 4, 2, 64, 3, false, MODE>(st, A, W, m_base, M, Nout, K, ep, slots);
   }
 }
 
@@ -610,7 +665,8 @@ hipError_t launch_mode(const nova_ctx* ctx, hipStream_t st, const bf16_t* A, con
                        int K, const EpiParams<bf16_t>& ep) {
   const Plan p = plan_rows(ctx, MODE, M, Nout, K);
   for (int i = 0; i < p.n; ++i) {
-    const hipError_t e = launch_part<MODE>(st, p.cfg[i], A, W, p.m_base[i], p.m_end[i], Nout, K, ep);
+    const hipError_t e = launch_part<MODE>(st, p.cfg[i], A, W, p.m_base[i], p.m_end[i], Nout, K, ep,
+                                           (ctx && ctx->gemm_persist == 0) ? 0 : (ctx ? ctx->num_cus : 256));
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
