@@ -5,7 +5,11 @@
 // One 1024-thread workgroup per batch row.  Entropies are mapped to 32-bit keys whose
 // unsigned order is the required numeric order (NaN lowest, -0 == +0), staged in LDS,
 // and the k-th largest key is found by a 4-pass, 8-bit MSB radix select on LDS
-// histograms.  Every key above the threshold is kept; of the keys equal to it the
+// histograms.  Entropies of one row share their leading bits, so in the first passes
+// nearly all keys fall into one or two bins: a single histogram would serialise its
+// atomics on one address.  Each bin therefore has 32 counters, one per LDS bank, and a
+// lane adds to the counter of its own bank; the 32 counters are summed (and cleared)
+// after the pass.  Every key above the threshold is kept; of the keys equal to it the
 // first (k - #above) in index order are kept.  Two block-wide prefix sums over
 // contiguous index ranges turn that rule into the ascending index list and the mask.
 // Integer compares only: the result equals a stable sort bit for bit.
@@ -17,6 +21,8 @@ namespace {
 constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / NOVA_WAVE;
 constexpr int kLdsKeys = 8192;   // rows up to this many tokens are staged in LDS
+constexpr int kCopies = 32;      // counters per histogram bin, one per LDS bank
+static_assert(kThreads == 256 * 4, "the counter sum below gives four threads to every bin");
 
 __device__ __forceinline__ uint32_t sort_key(float h) {
   uint32_t b = __float_as_uint(h);
@@ -56,6 +62,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restric
                                                           uint8_t* __restrict__ mask) {
   __shared__ uint32_t keys_lds[STAGED ? kLdsKeys : 1];
   __shared__ uint32_t hist[256];
+  __shared__ uint32_t hist_banked[256 * kCopies];   // [bin][copy]: copy = lane % 32 = the LDS bank
   __shared__ uint32_t wave_sums[kWaves];
   __shared__ uint32_t sh_bin, sh_remaining;
 
@@ -85,12 +92,29 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restric
   bool keep_all_ge = true;     // false when k == 0: nothing is kept
   if (k == 0) keep_all_ge = false;
   if (k > 0 && k < N) {
+    for (int i = tid; i < 256 * kCopies; i += kThreads) hist_banked[i] = 0;
     for (int shift = 24; shift >= 0; shift -= 8) {
-      if (tid < 256) hist[tid] = 0;
       __syncthreads();
       for (int i = tid; i < N; i += kThreads) {
         uint32_t key = key_at(i);
-        if ((key & prefix_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        if ((key & prefix_mask) == prefix)
+          atomicAdd(&hist_banked[((key >> shift) & 255u) * kCopies + (lane & (kCopies - 1))], 1u);
+      }
+      __syncthreads();
+      {
+        // four threads per bin, eight counters each (walked from a bin-dependent start, so that the lanes of a
+        // wave touch all banks); the counters are left at zero for the next pass
+        const int bin = tid >> 2, q = tid & 3;
+        uint32_t s = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int c = bin * kCopies + q * 8 + ((j + bin) & 7);
+          s += hist_banked[c];
+          hist_banked[c] = 0;
+        }
+        s += __shfl_xor(s, 1, NOVA_WAVE);
+        s += __shfl_xor(s, 2, NOVA_WAVE);
+        if (q == 0) hist[bin] = s;
       }
       __syncthreads();
       if (wave == 0) {
@@ -116,7 +140,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restric
       prefix |= sh_bin << shift;
       prefix_mask |= 255u << shift;
       remaining = sh_remaining;
-      // hist is zeroed again only after the next barrier pair, sh_* rewritten after two more
+      // hist and sh_* are rewritten only behind further barriers of the next pass
     }
   } else if (k == N) {
     prefix = 0; remaining = 0;       // every key >= 0: all kept through the "above" rule below
