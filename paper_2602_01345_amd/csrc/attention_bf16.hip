@@ -230,43 +230,56 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
     }
 
     // ---- online softmax; register r of block kb is key key0 + kb*32 + 16*(r/8) + 8*half + r%8 ---
+    // The running maximum m_run is a reference point, not necessarily the maximum: the tile's
+    // probabilities are taken against it as it stands, and only when a lane's sum of them says that some
+    // score lies far above it (or m_run is still -inf: the first tile) is the true maximum of the tile
+    // computed, the accumulators rescaled and the tile's probabilities taken again.  Any common reference
+    // cancels in o / l at the end; a term of at most kBig keeps every sum far inside the fp32 range.  In
+    // the common case this saves the maximum pass over the scores.
+    constexpr float kBig = 1024.0f;
     bf16x8 p[NQ][4];
 #pragma unroll
     for (int g = 0; g < NQ; ++g) {
-      float tmax = -INFINITY;
+      if (TAIL) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          if (TAIL) {
+          for (int r = 0; r < 16; ++r) {
             const int key = key0 + kb * 32 + 16 * (r >> 3) + 8 * half + (r & 7);
             s[g][kb][r] = key < kv_total ? s[g][kb][r] : -INFINITY;
           }
-          tmax = fmaxf(tmax, s[g][kb][r]);
-        }
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, NOVA_WAVE));
-      const float m_new = fmaxf(m_run[g], tmax);        // finite: every tile holds a valid key
-      const float mb = m_new * scale_log2;
-      float psum = 0.f;
+      }
+      auto probabilities = [&](float mb) {
+        float psum = 0.f;
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float e = __builtin_amdgcn_exp2f(fmaf(s[g][kb][r], scale_log2, -mb));
-          psum += e;
-          p[g][kb * 2 + (r >> 3)][r & 7] = (bf16_t)e;
-        }
-      // rescale only when some query of the wave saw a new maximum (rare after the first tiles)
-      if (__any(m_new != m_run[g])) {
-        const float alpha = __builtin_amdgcn_exp2f((m_run[g] - m_new) * scale_log2);
+          for (int r = 0; r < 16; ++r) {
+            const float e = __builtin_amdgcn_exp2f(fmaf(s[g][kb][r], scale_log2, -mb));
+            psum += e;
+            p[g][kb * 2 + (r >> 3)][r & 7] = (bf16_t)e;
+          }
+        return psum;
+      };
+      float psum = probabilities(m_run[g] * scale_log2);
+      if (__any(!(psum <= kBig))) {             // also true for inf and NaN (m_run == -inf)
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[g][kb][r]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, NOVA_WAVE));
+        const float m_new = fmaxf(m_run[g], tmax);        // finite: every tile holds a valid key
+        const float alpha = __builtin_amdgcn_exp2f((m_run[g] - m_new) * scale_log2);   // 0 for m_run == -inf
         l_run[g] *= alpha;
 #pragma unroll
         for (int d = 0; d < DB; ++d)
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[g][d][r] *= alpha;
+        m_run[g] = m_new;
+        psum = probabilities(m_new * scale_log2);
       }
       l_run[g] += psum;
-      m_run[g] = m_new;
     }
 
     // ---- O^T += V^T P^T : DH rows x 32 queries per group, 4 runs of 16 keys --------------------

@@ -305,6 +305,37 @@ def test_block_bf16_key_range_edges(hx, P, k):
     _say(f"   errors {errs}")
 
 
+@pytest.mark.parametrize("dh_case", [(128, 2), (256, 2)])
+@pytest.mark.parametrize("forced_split", [0, 3])
+def test_block_bf16_peaked_attention_with_rising_scores(hx, dh_case, forced_split, monkeypatch):
+    """Sharply peaked attention whose largest score keeps rising along the keys: the query projection is scaled
+    up (scores spread over tens of nats) and the prior keys grow in length with their position, so that the
+    softmax reference point of the kernel has to move several times while it walks the key tiles, also inside
+    the runs of a split item."""
+    C, heads = dh_case
+    if forced_split:
+        from paper_2602_01345_amd import Nova
+        monkeypatch.setenv("NOVA_ATTN_SPLIT", str(forced_split))
+        monkeypatch.setattr(hx, "_NOVA", Nova(0))
+    _say(f"block bf16 peaked attention C={C} heads={heads} split={forced_split}")
+    wl = _custom("bf16", B=2, grid=17, prev=13, P=1500, C=C, heads=heads)
+    hb = hx.make_host_block(wl, 0, k=150)
+    w = hb.weights["w_qkv"].to(torch.float32)
+    w[:C] *= 24.0                                                     # query rows of [3C, C]
+    hb.weights["w_qkv"] = w.to(hb.weights["w_qkv"].dtype)
+    ramp = torch.linspace(0.25, 4.0, hb.k_prior.shape[1]).reshape(1, -1, 1)
+    hb.k_prior = (hb.k_prior.to(torch.float32) * ramp).to(hb.k_prior.dtype)
+    # the scores must really be spread: oracle-side check of the spread on one image and head
+    x0 = hb.x[0].to(torch.float64)
+    u = (x0 - x0.mean(-1, keepdim=True)) / torch.sqrt(x0.var(-1, unbiased=False, keepdim=True) + 1e-6)
+    dh = C // heads
+    q = (u @ hb.weights["w_qkv"].to(torch.float64)[:dh].T)            # head 0 queries, biases aside
+    sc = (q @ hb.k_prior[0, :, :dh].to(torch.float64).T) / dh ** 0.5
+    assert float(sc.max() - sc.median()) > 25.0, "the case no longer produces peaked attention"
+    errs = hx.check_block(hb, hx.BF16_TOL)
+    _say(f"   errors {errs}")
+
+
 @pytest.mark.parametrize("split", [2, 3, 4])
 def test_block_bf16_forced_key_splits(hx, split, monkeypatch):
     """The split-key attention path (partial sums merged by the combine kernel) with every split count."""
