@@ -53,7 +53,7 @@ __device__ __forceinline__ int swz(int r, int c) {
 template <int DH, int NQ, int NST, int OCC, int NW>
 __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc, int k, int C,
-    int heads, int cap, int kv_total, int nqb, int n_whole, int nsplit, float scale_log2,
+    int heads, int cap, int kv_total, int nqb, int n_whole, int nsplit,
     bf16_t* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml) {
   constexpr int KROWB = DH * 2;                  // bytes per key row of the K tile
   constexpr int KCH = KROWB / 16;                // chunks per key row
@@ -155,9 +155,19 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
     for (int d = 0; d < DB; ++d)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[g][d][r] = 0.f;
+  // Softmax state per query (= per lane).  The query rows arrive multiplied by (score scale * log2 e), so the
+  // MFMA sums are scores in log2 units.  m_run is the reference point the probabilities are taken against,
+  // 2^(score - m_run); neg_m holds -m_run in all 16 registers of an accumulator block and is the accumulator
+  // input of the first score MFMA of every tile, so the scores come out of the matrix core with the reference
+  // already subtracted.  Reference 0 until the first tile has set it.
   float m_run[NQ], l_run[NQ];
+  f32x16 neg_m[NQ];
 #pragma unroll
-  for (int g = 0; g < NQ; ++g) { m_run[g] = -INFINITY; l_run[g] = 0.f; }
+  for (int g = 0; g < NQ; ++g) {
+    m_run[g] = 0.f; l_run[g] = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) neg_m[g][r] = 0.f;
+  }
 
   // this workgroup's run of key tiles [t_begin, t_end)
   const int ntiles_all = (kv_total + BKV - 1) / BKV;
@@ -194,12 +204,6 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
     constexpr int GF = 4;                     // fragments per group
     static_assert(NF % GF == 0, "groups tile the fragments");
     f32x16 s[NQ][2];
-#pragma unroll
-    for (int g = 0; g < NQ; ++g)
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[g][kb][r] = 0.f;
     bf16x8 kf[2][GF];
     auto read_k = [&](int buf, int f0) {
 #pragma unroll
@@ -214,7 +218,8 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
         if (i >= lo && i < hi) {
           const int f = f0 + i;
 #pragma unroll
-          for (int g = 0; g < NQ; ++g) s[g][f / KSTEPS] = mfma32(kf[buf][i], qf[g][f % KSTEPS], s[g][f / KSTEPS]);
+          for (int g = 0; g < NQ; ++g)
+            s[g][f / KSTEPS] = mfma32(kf[buf][i], qf[g][f % KSTEPS], f % KSTEPS == 0 ? neg_m[g] : s[g][f / KSTEPS]);
         }
     };
     read_k(0, 0);
@@ -230,12 +235,12 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
     }
 
     // ---- online softmax; register r of block kb is key key0 + kb*32 + 16*(r/8) + 8*half + r%8 ---
-    // The running maximum m_run is a reference point, not necessarily the maximum: the tile's
-    // probabilities are taken against it as it stands, and only when a lane's sum of them says that some
-    // score lies far above it (or m_run is still -inf: the first tile) is the true maximum of the tile
-    // computed, the accumulators rescaled and the tile's probabilities taken again.  Any common reference
-    // cancels in o / l at the end; a term of at most kBig keeps every sum far inside the fp32 range.  In
-    // the common case this saves the maximum pass over the scores.
+    // s holds score - m_run.  m_run is a reference point, not necessarily the maximum: the tile's
+    // probabilities 2^s are taken against it as it stands, and only when a lane's sum of them says that some
+    // score lies far above it -- or on the first tile of the run, which sets it -- is the true maximum of the
+    // tile computed, the accumulators rescaled and the tile's probabilities taken again.  Any common
+    // reference cancels in o / l at the end; a term of at most kBig keeps every sum far inside the fp32
+    // range.  In the common case the softmax is one exp2, one add and half a conversion per score.
     constexpr float kBig = 1024.0f;
     bf16x8 p[NQ][4];
 #pragma unroll
@@ -249,35 +254,44 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
             s[g][kb][r] = key < kv_total ? s[g][kb][r] : -INFINITY;
           }
       }
-      auto probabilities = [&](float mb) {
-        float psum = 0.f;
+      float psum = 0.f;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float e = __builtin_amdgcn_exp2f(fmaf(s[g][kb][r], scale_log2, -mb));
-            psum += e;
-            p[g][kb * 2 + (r >> 3)][r & 7] = (bf16_t)e;
-          }
-        return psum;
-      };
-      float psum = probabilities(m_run[g] * scale_log2);
-      if (__any(!(psum <= kBig))) {             // also true for inf and NaN (m_run == -inf)
-        float tmax = -INFINITY;
+        for (int r = 0; r < 16; ++r) {
+          const float e = __builtin_amdgcn_exp2f(s[g][kb][r]);
+          psum += e;
+          p[g][kb * 2 + (r >> 3)][r & 7] = (bf16_t)e;
+        }
+      const bool first = t == t_begin;
+      if (__any(!(psum <= kBig)) || first) {    // !(<=) is also true for inf and NaN
+        float tmax = -INFINITY;                 // of score - m_run
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
           for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[g][kb][r]);
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, NOVA_WAVE));
-        const float m_new = fmaxf(m_run[g], tmax);        // finite: every tile holds a valid key
-        const float alpha = __builtin_amdgcn_exp2f((m_run[g] - m_new) * scale_log2);   // 0 for m_run == -inf
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, NOVA_WAVE));    // finite: every tile holds a valid key
+        // the reference moves by shift >= 0 (on the first tile: to the tile's maximum, whatever its sign;
+        // nothing has been accumulated yet, so there is nothing to rescale)
+        const float shift = first ? tmax : fmaxf(tmax, 0.f);
+        const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(-shift);
         l_run[g] *= alpha;
 #pragma unroll
         for (int d = 0; d < DB; ++d)
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[g][d][r] *= alpha;
-        m_run[g] = m_new;
-        psum = probabilities(m_new * scale_log2);
+        m_run[g] += shift;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) neg_m[g][r] = -m_run[g];
+        psum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float e = __builtin_amdgcn_exp2f(s[g][kb][r] - shift);
+            psum += e;
+            p[g][kb * 2 + (r >> 3)][r & 7] = (bf16_t)e;
+          }
       }
       l_run[g] += psum;
     }
@@ -374,7 +388,7 @@ constexpr int kCombineRows = 8;
 template <int DH, int BQ>
 __global__ __launch_bounds__(kCombineRows * (DH / 4)) void attention_combine_kernel(
     const float* __restrict__ part_o, const float* __restrict__ part_ml, int k, int C, int heads, int nqb,
-    int n_whole, int nsplit, float scale_log2, bf16_t* __restrict__ out) {
+    int n_whole, int nsplit, bf16_t* __restrict__ out) {
   constexpr int CHUNKS = BQ / kCombineRows;                         // workgroups per item
   const int ci = blockIdx.x / CHUNKS, chunk = blockIdx.x - ci * CHUNKS;
   const int item = n_whole + ci;
@@ -391,7 +405,7 @@ __global__ __launch_bounds__(kCombineRows * (DH / 4)) void attention_combine_ker
   float l = 0.f;
   for (int s = 0; s < nsplit; ++s) {
     const float* pm = part_ml + ((p0 + s) * BQ + qr) * 2;
-    const float w = __builtin_amdgcn_exp2f((pm[0] - mmax) * scale_log2);
+    const float w = __builtin_amdgcn_exp2f(pm[0] - mmax);        // references are in log2 units
     l = fmaf(w, pm[1], l);
     const f32x4 o = *reinterpret_cast<const f32x4*>(part_o + ((p0 + s) * BQ + qr) * DH + c);
     acc += w * o;
@@ -405,7 +419,7 @@ __global__ __launch_bounds__(kCombineRows * (DH / 4)) void attention_combine_ker
 
 template <int DH, int NQ, int NST, int OCC, int NW>
 hipError_t launch_cfg(const nova_ctx* ctx, hipStream_t st, const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int B,
-                      int k, int C, int heads, int cap, int kv_total, float scale_log2, bf16_t* out, float* part_o,
+                      int k, int C, int heads, int cap, int kv_total, bf16_t* out, float* part_o,
                       float* part_ml) {
   constexpr int BQ = NW * NQ * 32;
   const int nqb = (k + BQ - 1) / BQ;
@@ -455,10 +469,10 @@ hipError_t launch_cfg(const nova_ctx* ctx, hipStream_t st, const bf16_t* q, cons
   }
   const int grid = n_whole + (items - n_whole) * nsplit;
   attention_bf16_kernel<DH, NQ, NST, OCC, NW><<<grid, NW * 64, 0, st>>>(
-      q, kc, vc, k, C, heads, cap, kv_total, nqb, n_whole, nsplit, scale_log2, out, part_o, part_ml);
+      q, kc, vc, k, C, heads, cap, kv_total, nqb, n_whole, nsplit, out, part_o, part_ml);
   if (nsplit > 1)
     attention_combine_kernel<DH, BQ><<<(items - n_whole) * (BQ / kCombineRows), kCombineRows * (DH / 4), 0, st>>>(
-        part_o, part_ml, k, C, heads, nqb, n_whole, nsplit, scale_log2, out);
+        part_o, part_ml, k, C, heads, nqb, n_whole, nsplit, out);
   return hipGetLastError();
 }
 
@@ -468,20 +482,19 @@ int attention_max_split() { return kMaxSplit; }
 
 hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void* qv, const void* kcv,
                                  const void* vcv, int B, int k, int C, int heads, int cap, int kv_total,
-                                 float score_scale, void* outv, float* part_o, float* part_ml) {
+                                 void* outv, float* part_o, float* part_ml) {
   const bf16_t* q = static_cast<const bf16_t*>(qv);
   const bf16_t* kc = static_cast<const bf16_t*>(kcv);
   const bf16_t* vc = static_cast<const bf16_t*>(vcv);
   bf16_t* out = static_cast<bf16_t*>(outv);
   const int dh = C / heads;
-  const float scale_log2 = 1.4426950408889634f * score_scale;
   // One group of 32 queries per wave (two workgroups per CU, so that one wave's softmax overlaps
   // another wave's MFMAs); two groups per wave (half the LDS reads per MFMA, one workgroup per
   // CU) can be forced for tuning.
   int nq = ctx ? ctx->attn_cfg : -1;
   if (nq < 1 || nq > 3) nq = 1;   // 1: 4 waves x 32 queries (default); 2: 4 waves x 64 queries; 3: 8 waves x 32 queries, deeper ring
 #define ATT_LAUNCH(DH_, NQ_, NST_, OCC_, NW_)                                                                       \
-  return launch_cfg<DH_, NQ_, NST_, OCC_, NW_>(ctx, st, q, kc, vc, B, k, C, heads, cap, kv_total, scale_log2, out, \
+  return launch_cfg<DH_, NQ_, NST_, OCC_, NW_>(ctx, st, q, kc, vc, B, k, C, heads, cap, kv_total, out, \
                                                part_o, part_ml)
   if (dh == 64) {
     if (nq == 1) ATT_LAUNCH(64, 1, 2, 3, 4);

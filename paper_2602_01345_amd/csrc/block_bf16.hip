@@ -45,19 +45,21 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
   ep.gate_pitch = ada_pitch;
   ep.part = reinterpret_cast<float*>(ws.part_o);          // free once attention is done: K-slice sums of FFN2
 
+  // the attention kernel takes its query rows multiplied by (score scale * log2 e); unit-length queries get the
+  // factor when they are rescaled (a factor before that would cancel)
   ep.bias = static_cast<const bf16_t*>(w.b_qkv); ep.out = q; ep.ldo = C; ep.kc = kc; ep.vc = vc;
+  ep.q_scale = var.qk_norm ? 1.0f : kAttnLog2e / sqrtf((float)dh);
   {
     StageTimer t(ctx, st, NOVA_STAGE_QKV);
     e = launch_gemm_bf16(ctx, st, EPI_QKV, u, w.w_qkv, M, 3 * C, C, ep);
     if (e == hipSuccess && var.qk_norm)
-      e = launch_qk_norm(st, NOVA_BF16, q, kc, var.qk_scale, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len);
+      e = launch_qk_norm(st, NOVA_BF16, q, kc, var.qk_scale, kAttnLog2e, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len);
   }
   if (e != hipSuccess) return e;
 
   {
     StageTimer t(ctx, st, NOVA_STAGE_ATTENTION);
-    e = launch_attention_bf16(ctx, st, q, kc, vc, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len + s.k,
-                              var.qk_norm ? 1.0f : 1.0f / sqrtf((float)dh), attn,
+    e = launch_attention_bf16(ctx, st, q, kc, vc, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len + s.k, attn,
                               reinterpret_cast<float*>(ws.part_o), reinterpret_cast<float*>(ws.part_ml));
   }
   if (e != hipSuccess) return e;
@@ -75,10 +77,11 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
     e = launch_gather_ln(st, NOVA_BF16, x1, nullptr, M, s.k, s.N, C, nullptr, nullptr, 0, u);
     if (e != hipSuccess) return e;
     ep.bias = static_cast<const bf16_t*>(var.b_cq); ep.out = q; ep.ldo = C; ep.gate = nullptr;
+    ep.q_scale = kAttnLog2e / sqrtf((float)dh);
     e = launch_gemm_bf16(ctx, st, EPI_PLAIN, u, var.w_cq, M, C, C, ep);
     if (e != hipSuccess) return e;
     e = launch_attention_bf16(ctx, st, q, var.k_text, var.v_text, s.B, s.k, C, s.heads, var.text_capacity,
-                              var.text_len, 1.0f / sqrtf((float)dh), attn, reinterpret_cast<float*>(ws.part_o),
+                              var.text_len, attn, reinterpret_cast<float*>(ws.part_o),
                               reinterpret_cast<float*>(ws.part_ml));
     if (e != hipSuccess) return e;
     ep.bias = static_cast<const bf16_t*>(var.b_co); ep.out = x1; ep.ldo = C; ep.res = x1;

@@ -113,7 +113,7 @@ hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shap
     StageTimer t(ctx, st, NOVA_STAGE_QKV);
     gemm<EPI_QKV>(st, u, static_cast<const float*>(w.w_qkv), M, 3 * C, C, ep);
     if (var.qk_norm) {
-      e = launch_qk_norm(st, NOVA_F32, q, kc, var.qk_scale, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len);
+      e = launch_qk_norm(st, NOVA_F32, q, kc, var.qk_scale, 1.0f, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len);
       if (e != hipSuccess) return e;
     }
   }

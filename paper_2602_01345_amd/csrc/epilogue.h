@@ -34,6 +34,9 @@ struct EpiParams {
   int gate_pitch;
   // EPI_ENTROPY: [column tiles][M] partials (m, S, T, unused) with S = sum e^(x-m), T = sum (m-x) e^(x-m)
   f32x4* ent_part;
+  // bf16 kernels: factor on the query features (EPI_QKV: columns < C; EPI_PLAIN: all) before they are rounded --
+  // the attention kernel wants its queries multiplied by (score scale * log2 e)
+  float q_scale;
   // K slicing (few rows, long K): fp32 scratch for [slices][M][Nout] partial sums, or nullptr to forbid slicing
   float* part;
 };

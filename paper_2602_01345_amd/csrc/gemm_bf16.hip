@@ -375,6 +375,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
               float v = acc[i][jn][(2 * gp + g) * 4 + e] + bias[(2 * gp + g) * 4 + e];
               if (MODE == EPI_GELU) v = gelu_erf(v);
               if (MODE == EPI_GELU_TANH) v = gelu_tanh(v);
+              if (MODE == EPI_PLAIN) v *= ep.q_scale;
               o[e] = (bf16_t)v;
             }
             (g == 0 ? lo : hi) = __builtin_bit_cast(u32x2, o);
@@ -428,6 +429,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
     for (int g4 = 0; g4 < 4; ++g4) {
       const int lc = wn * (BN / WN) + jn * 32 + 8 * g4 + 4 * half;   // first of 4 consecutive features
       const int col = n0 + lc;
+      const float qs = col < ep.C ? ep.q_scale : 1.0f;   // query features (C is a multiple of 8: all four or none)
       float bias[4] = {0.f, 0.f, 0.f, 0.f};
       if (ep.bias && col < Nout) {
         const bf16x4 bv = *reinterpret_cast<const bf16x4*>(ep.bias + col);
@@ -439,7 +441,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
         const int lrw = wm * (BM / WM) + i * 32 + r32;
         bf16x4 o;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = (bf16_t)(acc[i][jn][g4 * 4 + e] + bias[e]);
+        for (int e = 0; e < 4; ++e) o[e] = (bf16_t)((acc[i][jn][g4 * 4 + e] + bias[e]) * qs);
         *reinterpret_cast<bf16x4*>(ct + lrw * CT_PITCH + lc) = o;
       }
     }

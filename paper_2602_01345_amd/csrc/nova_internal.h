@@ -86,7 +86,7 @@ hipError_t launch_gather_ln(hipStream_t st, int dtype, const void* src, const in
                             int N, int C, const void* shift, const void* scale, int mod_pitch, void* dst);
 // qk_norm.hip: queries [B*k, C] and the cache's key rows [P, P+k) scaled to unit length per head, in place;
 // the queries are also multiplied by qk_scale[head]
-hipError_t launch_qk_norm(hipStream_t st, int dtype, void* q, void* kc, const float* qk_scale, int B, int k, int C,
+hipError_t launch_qk_norm(hipStream_t st, int dtype, void* q, void* kc, const float* qk_scale, float q_mult, int B, int k, int C,
                           int heads, int cap, int P);
 
 // block_f32.hip: plain fp32 kernels (correctness path for small fp32 models)
@@ -102,12 +102,15 @@ size_t head_entropy_workspace_bytes(int M, int V);
 hipError_t launch_head_entropy(const nova_ctx* ctx, hipStream_t st, const void* hidden, const void* w_head,
                                const void* b_head, int rows_per_batch, int batch, int C, int V, float* H,
                                float* mean, void* workspace);
-// attention_bf16.hip: attn[B*k, C] = softmax(score_scale * q K^T) V per head over kv_total cached keys
+// attention_bf16.hip: attn[B*k, C] = softmax(ln 2 * q K^T) V per head over kv_total cached keys: the query rows
+// arrive multiplied by (score scale * log2 e) -- kAttnLog2e times the scale of the scores -- by whoever wrote
+// them (the projection's epilogue or the unit-length rescaling), so the kernel's scores are in log2 units
 // part_o / part_ml: workspace for split-key partial results (max_split * B * roundup(k, 256) * C and
 // ... * heads * 2 floats), or nullptr to forbid splitting
 int attention_max_split();
+constexpr float kAttnLog2e = 1.4426950408889634f;
 hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void* q, const void* kc, const void* vc,
-                                 int B, int k, int C, int heads, int cap, int kv_total, float score_scale, void* out,
+                                 int B, int k, int C, int heads, int cap, int kv_total, void* out,
                                  float* part_o, float* part_ml);
 // block_bf16.hip: MFMA path
 hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_shape& s,

@@ -14,7 +14,7 @@ constexpr float kNormFloor = 1e-12f;
 
 template <typename T>
 __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void qk_norm_kernel(
-    T* __restrict__ q, T* __restrict__ kc, const float* __restrict__ qk_scale, int M, int k, int C, int heads,
+    T* __restrict__ q, T* __restrict__ kc, const float* __restrict__ qk_scale, float q_mult, int M, int k, int C, int heads,
     int dh, int cap, int P) {
   const int lane = threadIdx.x & (NOVA_WAVE - 1);
   const int64_t item = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / NOVA_WAVE;   // (row m, head)
@@ -29,7 +29,7 @@ __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void qk_norm_kernel(
     sq = fmaf(a, a, sq);
     sk = fmaf(c, c, sk);
   }
-  const float fq = qk_scale[head] / fmaxf(sqrtf(wave_sum(sq)), kNormFloor);
+  const float fq = q_mult * qk_scale[head] / fmaxf(sqrtf(wave_sum(sq)), kNormFloor);
   const float fk = 1.0f / fmaxf(sqrtf(wave_sum(sk)), kNormFloor);
   for (int d = lane; d < dh; d += NOVA_WAVE) {
     qp[d] = (T)((float)qp[d] * fq);
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void qk_norm_kernel(
 // bf16, dh in {64, 128}: 16 bytes per lane, dh / 8 lanes per (row, head), several items per wave
 template <int DH>
 __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void qk_norm_bf16_kernel(
-    bf16_t* __restrict__ q, bf16_t* __restrict__ kc, const float* __restrict__ qk_scale, int M, int k, int C,
+    bf16_t* __restrict__ q, bf16_t* __restrict__ kc, const float* __restrict__ qk_scale, float q_mult, int M, int k, int C,
     int heads, int cap, int P) {
   constexpr int LPI = DH / 8;                 // lanes per item
   constexpr int IPW = NOVA_WAVE / LPI;        // items per wave
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void qk_norm_bf16_kernel
     sk += __shfl_xor(sk, o, NOVA_WAVE);
   }
   if (!live) return;
-  const float fq = qk_scale[head] / fmaxf(sqrtf(sq), kNormFloor);
+  const float fq = q_mult * qk_scale[head] / fmaxf(sqrtf(sq), kNormFloor);
   const float fk = 1.0f / fmaxf(sqrtf(sk), kNormFloor);
   bf16x8 qo, ko;
 #pragma unroll
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void qk_norm_bf16_kernel
 
 }  // namespace
 
-hipError_t launch_qk_norm(hipStream_t st, int dtype, void* q, void* kc, const float* qk_scale, int B, int k, int C,
+hipError_t launch_qk_norm(hipStream_t st, int dtype, void* q, void* kc, const float* qk_scale, float q_mult, int B, int k, int C,
                           int heads, int cap, int P) {
   const int M = B * k, dh = C / heads;
   const int64_t items = (int64_t)M * heads;
@@ -91,15 +91,15 @@ hipError_t launch_qk_norm(hipStream_t st, int dtype, void* q, void* kc, const fl
     const unsigned gridv = (unsigned)((items + ipb - 1) / ipb);
     if (dh == 64)
       qk_norm_bf16_kernel<64><<<gridv, kWavesPerBlock * NOVA_WAVE, 0, st>>>(
-          static_cast<bf16_t*>(q), static_cast<bf16_t*>(kc), qk_scale, M, k, C, heads, cap, P);
+          static_cast<bf16_t*>(q), static_cast<bf16_t*>(kc), qk_scale, q_mult, M, k, C, heads, cap, P);
     else
       qk_norm_bf16_kernel<128><<<gridv, kWavesPerBlock * NOVA_WAVE, 0, st>>>(
-          static_cast<bf16_t*>(q), static_cast<bf16_t*>(kc), qk_scale, M, k, C, heads, cap, P);
+          static_cast<bf16_t*>(q), static_cast<bf16_t*>(kc), qk_scale, q_mult, M, k, C, heads, cap, P);
   } else if (dtype == NOVA_BF16)
     qk_norm_kernel<bf16_t><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(
-        static_cast<bf16_t*>(q), static_cast<bf16_t*>(kc), qk_scale, M, k, C, heads, dh, cap, P);
+        static_cast<bf16_t*>(q), static_cast<bf16_t*>(kc), qk_scale, q_mult, M, k, C, heads, dh, cap, P);
   else
     qk_norm_kernel<float><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(
-        static_cast<float*>(q), static_cast<float*>(kc), qk_scale, M, k, C, heads, dh, cap, P);
+        static_cast<float*>(q), static_cast<float*>(kc), qk_scale, q_mult, M, k, C, heads, dh, cap, P);
   return hipGetLastError();
 }
