@@ -234,6 +234,31 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
       __builtin_amdgcn_sched_barrier(0);
     }
 
+    // Value fragments go through the same kind of register ring: one group = the DB fragments of a run of 16
+    // keys.  The first group is requested here, so that it lands behind the softmax arithmetic.
+    bf16x8 vf[2][DB];
+    bf16x8 p[NQ][4];                          // probabilities, in the B-operand layout of the value MFMAs
+    auto read_v = [&](int buf, int kg) {
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+        vf[buf][d] = *reinterpret_cast<const bf16x8*>(sv + swz<128>(d * 32 + col, kg * 2 + half));
+    };
+    auto mfma_v = [&](int buf, int kg, int lo, int hi) {
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+        if (d >= lo && d < hi) {
+#pragma unroll
+          for (int g = 0; g < NQ; ++g) o[g][d] = mfma32(vf[buf][d], p[g][kg], o[g][d]);
+        }
+    };
+    // (only where the register budget allows it: dh = 128 with one query group per wave; the other shapes read
+    // each fragment in front of its MFMA)
+    constexpr bool VRING = DB == 4 && NQ == 1;
+    if constexpr (VRING) {
+      read_v(0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+
     // ---- online softmax; register r of block kb is key key0 + kb*32 + 16*(r/8) + 8*half + r%8 ---
     // s holds score - m_run.  m_run is a reference point, not necessarily the maximum: the tile's
     // probabilities 2^s are taken against it as it stands, and only when a lane's sum of them says that some
@@ -242,7 +267,6 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
     // reference cancels in o / l at the end; a term of at most kBig keeps every sum far inside the fp32
     // range.  In the common case the softmax is one exp2, one add and half a conversion per score.
     constexpr float kBig = 1024.0f;
-    bf16x8 p[NQ][4];
 #pragma unroll
     for (int g = 0; g < NQ; ++g) {
       if (TAIL) {
@@ -297,14 +321,25 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
     }
 
     // ---- O^T += V^T P^T : DH rows x 32 queries per group, 4 runs of 16 keys --------------------
+    // pinned like the score MFMAs: first MFMA of a run, the reads of the next run, the run's other MFMAs
+    if constexpr (VRING) {
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int kg = 0; kg < 4; ++kg)
-#pragma unroll
-      for (int d = 0; d < DB; ++d) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(sv + swz<128>(d * 32 + col, kg * 2 + half));
-#pragma unroll
-        for (int g = 0; g < NQ; ++g) o[g][d] = mfma32(a, p[g][kg], o[g][d]);
+      for (int kg = 0; kg < 4; ++kg) {
+        mfma_v(kg & 1, kg, 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kg + 1 < 4) read_v((kg + 1) & 1, kg + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_v(kg & 1, kg, 1, DB);
+        __builtin_amdgcn_sched_barrier(0);
       }
+    } else {
+#pragma unroll
+      for (int kg = 0; kg < 4; ++kg) {
+        read_v(0, kg);
+        mfma_v(0, kg, 0, DB);
+      }
+    }
 
     // tile t+1 must have landed; this wave's LDS reads of the current stage must be complete
     if (more) { WAIT_VMCNT((NST - 2) * LPW); } else { WAIT_VMCNT(0); }
