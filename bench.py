@@ -202,6 +202,15 @@ def variant_step(nova, runner, wl, x, gen, dtype, steps):
         return (time.perf_counter() - t0) / steps * 1e3
 
     res["base_ms_per_step"] = round(timed_step(), 3)
+    # a model with unit-length queries and keys holds unit-length keys in its cache: the prior rows are rescaled
+    # for this measurement and put back afterwards (un-normalised keys times the per-head multiplier would make
+    # the scores tens of nats wide, which no such model produces)
+    P = runner.kv_len
+    saved = []
+    for st in runner.blocks:
+        prior = st.k_cache[:, :, :P, :]
+        saved.append(prior.clone())
+        prior.copy_(torch.nn.functional.normalize(prior.to(torch.float32), dim=-1).to(dtype))
     for st in runner.blocks:
         ada = rnd((wl.B, 6, wl.C), 0.2)
         ada[:, 2] += 1.0
@@ -213,8 +222,10 @@ def variant_step(nova, runner, wl, x, gen, dtype, steps):
         st.variant = BlockVariant(gelu_tanh=True, qk_scale=torch.rand(wl.heads, generator=gen, device="cuda") * 12 + 4,
                                   ada=ada, cross=cross)
     res["ms_per_step"] = round(timed_step(), 3)
-    for st in runner.blocks:
+    for st, prior in zip(runner.blocks, saved):
         st.variant = None
+        st.k_cache[:, :, :P, :].copy_(prior)
+    del saved
     s, st = wl.last, runner.blocks[len(runner.blocks) // 2]
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for interp, name in ((0, "bilinear"), (1, "nearest"), (2, "bicubic")):
