@@ -7,8 +7,11 @@
 //   O^T += V^T P^T A operand = value-cache columns from LDS (the value cache is stored key-minor
 //                  for exactly this read), B operand = the probabilities just computed, already
 //                  sitting in the lane layout the MFMA wants
-// so the online-softmax state (running max and sum) is one scalar per lane and query group, and
+// so the online-softmax state (reference point and sum) is one scalar per lane and query group, and
 // no data is exchanged between lanes except one max/sum swap between the two half-waves.
+// The query rows arrive multiplied by (score scale * log2 e): the MFMA sums are scores in log2 units, the
+// softmax reference enters as the accumulator input of the score MFMAs and moves only when a score lies far
+// above it, so per score the common case is one exp2, one add and half a conversion (see the tile body).
 //
 // A workgroup is NW (4 or 8) waves; a wave owns NQ groups of 32 queries (every K / V fragment read from LDS
 // feeds NQ MFMAs).  K and V tiles of 64 keys stream through an NST-stage LDS ring filled by
