@@ -184,6 +184,9 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
   if (t_begin + 1 == ntiles_all && kv_total < ntiles_all * BKV) zero_value_tail(0, t_begin * BKV);
   __syncthreads();
 
+  // The last query block of an (image, head) is ragged: waves with no kept query leave the matrix core and the
+  // vector units to the other workgroup of the CU.
+  const bool wave_live = qb * BQ + wave * NQ * 32 < k;
   // A-operand row of this lane inside a 32-key block (see key_of_mfma_row)
   const int krow = key_of_mfma_row(col);
   // One 64-key tile.  TAIL (last tile only) masks the scores of keys past kv_total.  stage_v is the ring stage
@@ -199,6 +202,7 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
     const char* sk = lds + stage * STAGE;
     const char* sv = sk + K_BYTES;
 
+    if (wave_live) {   // a wave whose queries all lie past the last kept row only helps to fill and to synchronise
     // ---- S^T tile: 64 keys x 32 queries per group, two 32-key blocks -------------------------
     // Key fragments travel through a two-deep register ring of GF fragments.  The schedule is
     // pinned: first MFMA of a group, then the LDS reads of the next group, then the group's other
@@ -343,6 +347,7 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
         mfma_v(0, kg, 0, DB);
       }
     }
+    }   // wave_live
 
     // tile t+1 must have landed; this wave's LDS reads of the current stage must be complete
     if (more) { WAIT_VMCNT((NST - 2) * LPW); } else { WAIT_VMCNT(0); }
