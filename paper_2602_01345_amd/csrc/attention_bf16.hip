@@ -241,26 +241,32 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
       __builtin_amdgcn_sched_barrier(0);
     }
 
-    // Value fragments go through the same kind of register ring: one group = the DB fragments of a run of 16
-    // keys.  The first group is requested here, so that it lands behind the softmax arithmetic.
-    bf16x8 vf[2][DB];
+    // Value fragments go through the same kind of register ring: one group = four fragments = the DB fragments
+    // of 4 / DB runs of 16 keys.  The first group is requested here, so that it lands behind the softmax
+    // arithmetic.
+    constexpr int KGG = 4 / DB;               // key runs per group
+    constexpr int NG = 4 / KGG;               // groups per tile
+    bf16x8 vf[2][4];
     bf16x8 p[NQ][4];                          // probabilities, in the B-operand layout of the value MFMAs
-    auto read_v = [&](int buf, int kg) {
+    auto read_v = [&](int buf, int grp) {
 #pragma unroll
-      for (int d = 0; d < DB; ++d)
-        vf[buf][d] = *reinterpret_cast<const bf16x8*>(sv + swz<128>(d * 32 + col, kg * 2 + half));
+      for (int f = 0; f < 4; ++f) {
+        const int kg = grp * KGG + f / DB, d = f % DB;
+        vf[buf][f] = *reinterpret_cast<const bf16x8*>(sv + swz<128>(d * 32 + col, kg * 2 + half));
+      }
     };
-    auto mfma_v = [&](int buf, int kg, int lo, int hi) {
+    auto mfma_v = [&](int buf, int grp, int lo, int hi) {
 #pragma unroll
-      for (int d = 0; d < DB; ++d)
-        if (d >= lo && d < hi) {
+      for (int f = 0; f < 4; ++f)
+        if (f >= lo && f < hi) {
+          const int kg = grp * KGG + f / DB, d = f % DB;
 #pragma unroll
-          for (int g = 0; g < NQ; ++g) o[g][d] = mfma32(vf[buf][d], p[g][kg], o[g][d]);
+          for (int g = 0; g < NQ; ++g) o[g][d] = mfma32(vf[buf][f], p[g][kg], o[g][d]);
         }
     };
-    // (only where the register budget allows it: dh = 128 with one query group per wave; the other shapes read
-    // each fragment in front of its MFMA)
-    constexpr bool VRING = DB == 4 && NQ == 1;
+    // (only where the register budget allows it: one query group per wave and at most two workgroups per CU;
+    // otherwise the fragments are read in front of their MFMAs)
+    constexpr bool VRING = NQ == 1 && OCC <= 2;
     if constexpr (VRING) {
       read_v(0, 0);
       __builtin_amdgcn_sched_barrier(0);
@@ -332,19 +338,19 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
     if constexpr (VRING) {
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int kg = 0; kg < 4; ++kg) {
-        mfma_v(kg & 1, kg, 0, 1);
+      for (int grp = 0; grp < NG; ++grp) {
+        mfma_v(grp & 1, grp, 0, 1);
         __builtin_amdgcn_sched_barrier(0);
-        if (kg + 1 < 4) read_v((kg + 1) & 1, kg + 1);
+        if (grp + 1 < NG) read_v((grp + 1) & 1, grp + 1);
         __builtin_amdgcn_sched_barrier(0);
-        mfma_v(kg & 1, kg, 1, DB);
+        mfma_v(grp & 1, grp, 1, 4);
         __builtin_amdgcn_sched_barrier(0);
       }
     } else {
 #pragma unroll
-      for (int kg = 0; kg < 4; ++kg) {
-        read_v(0, kg);
-        mfma_v(0, kg, 0, DB);
+      for (int grp = 0; grp < NG; ++grp) {
+        read_v(0, grp);
+        mfma_v(0, grp, 0, 4);
       }
     }
     }   // wave_live
@@ -535,12 +541,15 @@ hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void
   // another wave's MFMAs); two groups per wave (half the LDS reads per MFMA, one workgroup per
   // CU) can be forced for tuning.
   int nq = ctx ? ctx->attn_cfg : -1;
-  if (nq < 1 || nq > 3) nq = 1;   // 1: 4 waves x 32 queries (default); 2: 4 waves x 64 queries; 3: 8 waves x 32 queries, deeper ring
+  // 1: 4 waves x 32 queries, two workgroups per CU (default); 2: 4 waves x 64 queries; 3: 8 waves x 32 queries,
+  // deeper ring; 4 (dh = 64 only): as 1 with three workgroups per CU and no value-fragment ring
+  if (nq < 1 || nq > 4) nq = 1;
 #define ATT_LAUNCH(DH_, NQ_, NST_, OCC_, NW_)                                                                       \
   return launch_cfg<DH_, NQ_, NST_, OCC_, NW_>(ctx, st, q, kc, vc, B, k, C, heads, cap, kv_total, out, \
                                                part_o, part_ml)
   if (dh == 64) {
-    if (nq == 1) ATT_LAUNCH(64, 1, 2, 3, 4);
+    if (nq == 1) ATT_LAUNCH(64, 1, 2, 2, 4);
+    if (nq == 4) ATT_LAUNCH(64, 1, 2, 3, 4);
     if (nq == 3) ATT_LAUNCH(64, 1, 4, 2, 8);
     ATT_LAUNCH(64, 2, 3, 1, 4);
   }
