@@ -15,6 +15,50 @@ namespace {
 constexpr int kWavesPerBlock = 4;
 constexpr int kUnroll = 4;
 
+// Position of kept token i in the ascending kept list of its image = the number of kept tokens in front of it.
+// When the image's mask row is 16-byte aligned and a whole number of 16-byte chunks, the wave counts the
+// non-zero mask bytes before i, 16 per lane and step: independent loads, one round trip to memory.  Otherwise a
+// binary search over the index list (log2 k dependent loads).  Both give the same number for a consistent
+// (index list, mask) pair.  Wave-uniform result.
+__device__ __forceinline__ int kept_rank(const uint8_t* __restrict__ mrow, const int32_t* __restrict__ list, int N,
+                                         int k, int i, int lane) {
+  if ((reinterpret_cast<uintptr_t>(mrow) & 15) == 0 && N % 16 == 0) {
+    int cnt = 0;
+    constexpr int kChunks = 4;                             // chunks per lane requested together
+    for (int base = 0; base < i; base += kChunks * NOVA_WAVE * 16) {
+      u32x4 v[kChunks];
+#pragma unroll
+      for (int u = 0; u < kChunks; ++u) {
+        const int j0 = base + (u * NOVA_WAVE + lane) * 16;
+        v[u] = u32x4{0u, 0u, 0u, 0u};
+        if (j0 < i) v[u] = *reinterpret_cast<const u32x4*>(mrow + j0);
+      }
+#pragma unroll
+      for (int u = 0; u < kChunks; ++u) {
+        const int j0 = base + (u * NOVA_WAVE + lane) * 16;
+        const int valid = min(16, i - j0);                 // bytes of this chunk that lie in front of i (<= 0: none)
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          const int nv = min(max(valid - 4 * d, 0), 4);
+          const uint32_t keep = nv >= 4 ? 0xffffffffu : ((1u << (8 * nv)) - 1u);
+          const uint32_t wd = v[u][d] & keep;
+          const uint32_t nz = (((wd & 0x7f7f7f7fu) + 0x7f7f7f7fu) | wd) & 0x80808080u;   // top bit of every non-zero byte
+          cnt += __popc(nz);
+        }
+      }
+    }
+#pragma unroll
+    for (int o = NOVA_WAVE / 2; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, NOVA_WAVE);
+    return min(cnt, k - 1);
+  }
+  int lo = 0, hi = k - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (list[mid] < i) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
 struct Taps {
   int i0, i1;
   float w1;
@@ -52,13 +96,7 @@ __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void merge_kernel(
   T* cnr = cache_new ? cache_new + row * C : nullptr;
 
   if (mask[row] && k > 0) {
-    // position of token i in the ascending kept list of this batch row
-    const int32_t* list = idx + (int64_t)b * k;
-    int lo = 0, hi = k - 1;
-    while (lo < hi) {
-      int mid = (lo + hi) >> 1;
-      if (list[mid] < i) lo = mid + 1; else hi = mid;
-    }
+    const int lo = kept_rank(mask + (int64_t)b * N, idx + (int64_t)b * k, N, k, i, lane);
     const T* yr = y + ((int64_t)b * k + lo) * C;
     for (int v0 = 0; v0 < nvec; v0 += kUnroll * NOVA_WAVE) {
       VT vy[kUnroll], vx[kUnroll];
@@ -193,12 +231,7 @@ __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void merge_taps_kernel(
   T* cnr = cache_new ? cache_new + row * C : nullptr;
 
   if (mask[row] && k > 0) {       // kept token: the block's output, copied; residual = output - input
-    const int32_t* list = idx + (int64_t)b * k;
-    int lo = 0, hi = k - 1;
-    while (lo < hi) {
-      int mid = (lo + hi) >> 1;
-      if (list[mid] < i) lo = mid + 1; else hi = mid;
-    }
+    const int lo = kept_rank(mask + (int64_t)b * N, idx + (int64_t)b * k, N, k, i, lane);
     const T* yr = y + ((int64_t)b * k + lo) * C;
     for (int vi = lane; vi < nvec; vi += NOVA_WAVE) {
       VT vy, vx, c;
