@@ -1,7 +1,7 @@
 // Row gather + LayerNorm (no affine, biased variance, eps 1e-6) feeding the block's
-// two projections; optionally modulated per image, LN(x) (1 + scale[b]) + shift[b].  One wave64 per row; mean and variance are two separate fp32
-// passes over the row (the second and third read hit the cache), the output is
-// rounded once to the storage type.
+// two projections; optionally modulated per image, LN(x) (1 + scale[b]) + shift[b].  One wave64 per row; mean and
+// variance are two separate fp32 passes over the row, which is read once and held in registers when it fits
+// (else three reads, the second and third from the cache); the output is rounded once to the storage type.
 #include "common.h"
 #include "nova_internal.h"
 
@@ -9,6 +9,7 @@ namespace {
 
 constexpr int kWavesPerBlock = 4;
 constexpr float kEps = 1e-6f;
+constexpr int kRegVecs = 8;        // 16-byte vectors per lane a row may take to be kept in registers
 
 template <typename T>
 __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void gather_ln_kernel(
@@ -28,6 +29,52 @@ __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void gather_ln_kernel(
   const T* p = src + srow * C;
   T* q = dst + (int64_t)m * C;
   const int nvec = C / VN;
+
+  if (nvec <= kRegVecs * NOVA_WAVE) {
+    // the row fits the wave's registers (C <= 4096 bf16 / 2048 fp32): read once; the same sums in the same
+    // order as the three-pass form below
+    VT v[kRegVecs];
+#pragma unroll
+    for (int u = 0; u < kRegVecs; ++u) {
+      const int vi = u * NOVA_WAVE + lane;
+      if (vi < nvec) v[u].load(p + vi * VN);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int u = 0; u < kRegVecs; ++u)
+      if (u * NOVA_WAVE + lane < nvec) {
+#pragma unroll
+        for (int e = 0; e < VN; ++e) sum += v[u].get(e);
+      }
+    const float mean = wave_sum(sum) / (float)C;
+    float sq = 0.f;
+#pragma unroll
+    for (int u = 0; u < kRegVecs; ++u)
+      if (u * NOVA_WAVE + lane < nvec) {
+#pragma unroll
+        for (int e = 0; e < VN; ++e) { float d = v[u].get(e) - mean; sq = fmaf(d, d, sq); }
+      }
+    const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)C + kEps);
+    const T* sh = shift ? shift + (int64_t)(m / k) * mod_pitch : nullptr;
+    const T* sc = shift ? scale + (int64_t)(m / k) * mod_pitch : nullptr;
+#pragma unroll
+    for (int u = 0; u < kRegVecs; ++u) {
+      const int vi = u * NOVA_WAVE + lane;
+      if (vi < nvec) {
+        VT o;
+        if (shift) {
+          VT a, g; a.load(sh + vi * VN); g.load(sc + vi * VN);
+#pragma unroll
+          for (int e = 0; e < VN; ++e) o.set(e, fmaf((v[u].get(e) - mean) * rstd, 1.0f + g.get(e), a.get(e)));
+        } else {
+#pragma unroll
+          for (int e = 0; e < VN; ++e) o.set(e, (v[u].get(e) - mean) * rstd);
+        }
+        o.store(q + vi * VN);
+      }
+    }
+    return;
+  }
 
   float sum = 0.f;
   for (int vi = lane; vi < nvec; vi += NOVA_WAVE) {
