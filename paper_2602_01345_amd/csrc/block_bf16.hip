@@ -43,7 +43,7 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
   ep.C = C; ep.heads = s.heads; ep.dh = dh; ep.cap = s.kv_capacity; ep.P = s.kv_len; ep.k = s.k;
   ep.idx = idx; ep.Ntok = s.N;
   ep.gate_pitch = ada_pitch;
-  ep.part = reinterpret_cast<float*>(ws.part_o);          // free once attention is done: K-slice sums of FFN2
+  ep.part = reinterpret_cast<float*>(ws.part_o);          // free once attention is done: K-slice sums of the projections back to C
 
   // the attention kernel takes its query rows multiplied by (score scale * log2 e); unit-length queries get the
   // factor when they are rescaled (a factor before that would cancel)

@@ -506,8 +506,10 @@ hipError_t launch_cfg(hipStream_t st, const bf16_t* A, const bf16_t* W, int m_ba
   return hipGetLastError();
 }
 
-// Second pass of a K-sliced launch: out = residual-epilogue(sum of the slices + bias) for rows [m_base, M).
+// Second pass of a K-sliced launch: out = residual-epilogue(sum of the slices + bias) for rows [m_base, M);
+// MODE is EPI_RESIDUAL (residual row = output row) or EPI_ATTN_OUT (residual row gathered through the kept indices).
 // One thread per 8 output features.
+template <int MODE>
 __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float* __restrict__ part, int kslices, int m_base,
                                                           int M, int Nout, EpiParams<bf16_t> ep) {
   const int cpr = Nout / 8;
@@ -525,7 +527,9 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float* __restric
 #pragma unroll
   for (int e = 0; e < 8; ++e) bias[e] = (bf16_t)0.f;
   if (ep.bias) bias = *reinterpret_cast<const bf16x8*>(ep.bias + col);
-  const bf16x8 r = *reinterpret_cast<const bf16x8*>(ep.res + (int64_t)row * ep.ldo + col);
+  int64_t roff = (int64_t)row * ep.ldo;
+  if (MODE == EPI_ATTN_OUT) roff = ((int64_t)(row / ep.k) * ep.Ntok + min(max(ep.idx[row], 0), ep.Ntok - 1)) * ep.C;
+  const bf16x8 r = *reinterpret_cast<const bf16x8*>(ep.res + roff + col);
   bf16x8 o;
   if (ep.gate) {
     const bf16x8 gt = *reinterpret_cast<const bf16x8*>(ep.gate + (int64_t)(row / ep.k) * ep.gate_pitch + col);
@@ -635,19 +639,19 @@ Plan plan_rows(const nova_ctx* ctx, int mode, int M, int Nout, int K) {
 template <int MODE>
 hipError_t launch_part(hipStream_t st, int cfg, const bf16_t* A, const bf16_t* W, int m_base, int M, int Nout, int K,
                        const EpiParams<bf16_t>& ep, int slots) {
-  if constexpr (MODE == EPI_RESIDUAL) {
-    // Few rows and a long K (the FFN down projection of the small scales and of row remainders): a tile column is
-    // one workgroup, too few to stream the weights at speed.  K is cut into slices summed by more workgroups; a
-    // second small pass adds the slices and applies the epilogue.
+  if constexpr (MODE == EPI_RESIDUAL || MODE == EPI_ATTN_OUT) {
+    // Few rows and a narrow output (the two projections back to C of the small scales and of row remainders): a
+    // tile column is one workgroup, too few to stream the weights at speed.  K is cut into slices summed by more
+    // workgroups (at least eight K steps per slice); a second small pass adds the slices and applies the epilogue.
     const int wgs = ((M - m_base + (cfg == 3 ? 63 : 127)) / (cfg == 3 ? 64 : 128)) * ((Nout + 31) / 32);
-    if ((cfg == 3 || cfg == 4) && ep.part && wgs <= 128 && K >= 4096 && K % (4 * 64) == 0 && Nout % 8 == 0) {
+    if ((cfg == 3 || cfg == 4) && ep.part && wgs <= 128 && K >= 2048 && K % (4 * 64) == 0 && Nout % 8 == 0) {
       const int ks = 4;
       const hipError_t e =
           cfg == 3 ? launch_cfg<64, 32, 2, 1, 64, 6, true, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, 0, ks)
                    : launch_cfg<128, 32, 4, 1, 64, 4, true, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, 0, ks);
       if (e != hipSuccess) return e;
       const int64_t nvec = (int64_t)(M - m_base) * (Nout / 8);
-      gemm_reduce_kernel<<<(unsigned)((nvec + 255) / 256), 256, 0, st>>>(ep.part, ks, m_base, M, Nout, ep);
+      gemm_reduce_kernel<MODE><<<(unsigned)((nvec + 255) / 256), 256, 0, st>>>(ep.part, ks, m_base, M, Nout, ep);
       return hipGetLastError();
     }
   }
