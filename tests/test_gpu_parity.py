@@ -199,6 +199,15 @@ def test_block_f32_small(hx, k):
     _say(f"   errors {errs}")
 
 
+def test_block_f32_rows_wider_than_the_layer_norm_register_path(hx):
+    """C = 2304 in fp32 is 576 16-byte vectors per row, more than a wave of the LayerNorm kernel keeps in
+    registers: the rows go through its three-pass form."""
+    _say("block f32 C=2304 k=3")
+    wl = _custom("f32", B=1, grid=4, prev=3, P=8, C=2304, heads=36)
+    errs = hx.check_block(hx.make_host_block(wl, 0, k=3), hx.F32_TOL)
+    _say(f"   errors {errs}")
+
+
 @pytest.mark.parametrize("k", [1, 40, 100])
 def test_block_bf16_few_rows_long_ffn(hx, k):
     """Few kept rows and an FFN hidden width of 4096: the down projection sums K in slices over several
