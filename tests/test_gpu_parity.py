@@ -361,6 +361,23 @@ def test_block_bf16_forced_key_splits(hx, split, monkeypatch):
     hx.check_block(hb, hx.BF16_TOL)
 
 
+@pytest.mark.parametrize("knob,value", [("NOVA_ATTN_CFG", "2"), ("NOVA_ATTN_CFG", "3"), ("NOVA_ATTN_CFG", "4"),
+                                        ("NOVA_GEMM_CFG", "0"), ("NOVA_GEMM_CFG", "1"), ("NOVA_GEMM_CFG", "2"),
+                                        ("NOVA_GEMM_CFG", "5"), ("NOVA_GEMM_CFG", "6"), ("NOVA_GEMM_PARTS", "0"),
+                                        ("NOVA_GEMM_PERSIST", "0")])
+def test_block_bf16_with_every_tuning_knob(hx, knob, value, monkeypatch):
+    """The kernel shapes that only an environment knob selects (other attention workgroup shapes, every GEMM tile
+    configuration forced, no two-launch row plans, one workgroup per tile) compute the same block."""
+    from paper_2602_01345_amd import Nova
+    monkeypatch.setenv(knob, value)
+    monkeypatch.setattr(hx, "_NOVA", Nova(0))          # the knobs are read when a context is created
+    _say(f"block bf16 with {knob}={value}")
+    for C, heads, P, k in ((128, 2, 300, 150), (512, 4, 700, 289)):      # dh = 64 and dh = 128, ragged everywhere
+        wl = _custom("bf16", B=2, grid=17, prev=13, P=P, C=C, heads=heads)
+        errs = hx.check_block(hx.make_host_block(wl, 0, k=k), hx.BF16_TOL)
+        _say(f"   C={C}: errors {errs}")
+
+
 def test_step_with_look_ahead_selection_equals_the_sequential_step(hx):
     """run_step enqueues every block's entropy + selection one block ahead on a second stream; the outputs must
     be those of the plain sequence, bit for bit, also when the step is repeated."""
