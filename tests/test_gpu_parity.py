@@ -424,3 +424,24 @@ def test_block_is_deterministic(hx):
                                          st.k_cache, st.v_cache)])
     for a, b in zip(*outs):
         assert torch.equal(a, b)
+
+
+def test_tile_walking_gemm_workgroups_give_the_same_bits_as_one_workgroup_per_tile(hx, monkeypatch):
+    """At the largest workload the projections with more tiles than CUs run one workgroup per CU that walks its
+    tiles; every tile is still summed in the same order, so the block's outputs are the same bits as with one
+    workgroup per tile (NOVA_GEMM_PERSIST=0)."""
+    from paper_2602_01345_amd import Nova
+    wl = WL.WORKLOADS["cfg5"]
+    hb = hx.make_host_block(wl, 0)
+    _say(f"cfg5 block 0, k={hb.k}: tile-walking workgroups against one workgroup per tile")
+    outs = []
+    for persist in ("1", "0"):
+        monkeypatch.setenv("NOVA_GEMM_PERSIST", persist)
+        monkeypatch.setattr(hx, "_NOVA", Nova(0))
+        runner, st, x = hx.to_gpu(hb)
+        runner.run_block(st, x)
+        torch.cuda.synchronize()
+        outs.append([t.clone() for t in (st.y_kept, st.out, st.cache_new)])
+        del runner, st, x
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
