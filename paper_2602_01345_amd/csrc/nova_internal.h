@@ -75,7 +75,7 @@ struct BlockWorkspace {
   char* x1;    // [M, C]  residual stream after attention
   char* hid;   // [M, F]  FFN hidden
   char* part_o;   // bf16 path: attention partial sums, fp32: max_split per item, [query block][dh] each
-  char* part_ml;  // bf16 path: their running max / sum per query
+  char* part_ml;  // bf16 path: their softmax reference point (log2 units) and sum per query
   size_t total;
 };
 BlockWorkspace carve_workspace(const nova_block_shape& s, void* base);
