@@ -90,6 +90,8 @@ int nova_create(nova_ctx** out, int device_id) {
   c->gemm_parts = gp ? atoi(gp) : -1;
   const char* gs = getenv("NOVA_GEMM_PERSIST");
   c->gemm_persist = gs ? atoi(gs) : -1;
+  const char* gk = getenv("NOVA_GEMM_KSPLIT");
+  c->gemm_ksplit = gk ? atoi(gk) : -1;
   *out = c;
   return NOVA_OK;
 }

@@ -638,7 +638,30 @@ Plan plan_rows(const nova_ctx* ctx, int mode, int M, int Nout, int K) {
 
 template <int MODE>
 hipError_t launch_part(hipStream_t st, int cfg, const bf16_t* A, const bf16_t* W, int m_base, int M, int Nout, int K,
-                       const EpiParams<bf16_t>& ep, int slots) {
+                       const EpiParams<bf16_t>& ep, int slots, int cus, int ksplit) {
+  if constexpr (MODE == EPI_RESIDUAL) {
+    // A long K and a narrow output with large tiles (the FFN down projection once few tokens are kept): the tiles
+    // fill less than half of the CUs.  K is cut into 2 or 4 slices summed by as many workgroups per tile, fp32
+    // partial sums go to the scratch buffer and the second pass adds them and applies the epilogue.  The scratch
+    // buffer holds 4 x rows x C floats, hence Nout == C and at most four slices.
+    if ((cfg == 2 || cfg == 5 || cfg == 6) && ep.part && ksplit != 0 && K >= 4096 && Nout == ep.C && Nout % 8 == 0) {
+      const int bm = cfg == 5 ? 128 : 256, bn = cfg == 6 ? 256 : 128, bk = cfg == 6 ? 32 : 64;
+      const int tiles = ((M - m_base + bm - 1) / bm) * ((Nout + bn - 1) / bn);
+      int ks = 1;
+      if (ksplit > 0) ks = ksplit;
+      else while (ks < 4 && tiles * ks * 2 <= cus) ks *= 2;
+      if ((ks == 2 || ks == 4) && K % (ks * bk) == 0 && K / (ks * bk) >= 16) {
+        hipError_t e;
+        if (cfg == 2) e = launch_cfg<256, 128, 4, 2, 64, 3, false, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, 0, ks);
+        else if (cfg == 5) e = launch_cfg<128, 128, 2, 2, 64, 3, false, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, 0, ks);
+        else e = launch_cfg<256, 256, 2, 4, 32, 3, false, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, 0, ks);
+        if (e != hipSuccess) return e;
+        const int64_t nvec = (int64_t)(M - m_base) * (Nout / 8);
+        gemm_reduce_kernel<MODE><<<(unsigned)((nvec + 255) / 256), 256, 0, st>>>(ep.part, ks, m_base, M, Nout, ep);
+        return hipGetLastError();
+      }
+    }
+  }
   if constexpr (MODE == EPI_RESIDUAL || MODE == EPI_ATTN_OUT) {
     // Few rows and a narrow output (the two projections back to C of the small scales and of row remainders): a
     // tile column is one workgroup, too few to stream the weights at speed.  K is cut into slices summed by more
@@ -671,8 +694,10 @@ hipError_t launch_mode(const nova_ctx* ctx, hipStream_t st, const bf16_t* A, con
                        int K, const EpiParams<bf16_t>& ep) {
   const Plan p = plan_rows(ctx, MODE, M, Nout, K);
   for (int i = 0; i < p.n; ++i) {
+    const int cus = ctx ? ctx->num_cus : 256;
     const hipError_t e = launch_part<MODE>(st, p.cfg[i], A, W, p.m_base[i], p.m_end[i], Nout, K, ep,
-                                           (ctx && ctx->gemm_persist == 0) ? 0 : (ctx ? ctx->num_cus : 256));
+                                           (ctx && ctx->gemm_persist == 0) ? 0 : cus, cus,
+                                           ctx ? ctx->gemm_ksplit : -1);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;

@@ -26,6 +26,7 @@ struct nova_ctx {
   int attn_split; // >= 1 forces the number of attention key splits (NOVA_ATTN_SPLIT)
   int gemm_parts; // 0 forbids splitting a GEMM's rows over two launches (NOVA_GEMM_PARTS)
   int gemm_persist; // 0: one workgroup per tile always (NOVA_GEMM_PERSIST); else one workgroup per CU walks several tiles
+  int gemm_ksplit;  // 0: never cut K of the large-tile FFN down projection into slices; 2 / 4: always (NOVA_GEMM_KSPLIT)
 };
 
 // Brackets one kernel launch with a pair of events when its stage is being timed.

@@ -378,6 +378,21 @@ def test_block_bf16_with_every_tuning_knob(hx, knob, value, monkeypatch):
         _say(f"   C={C}: errors {errs}")
 
 
+@pytest.mark.parametrize("ksplit", ["0", "2", "4", None])
+def test_block_bf16_ffn_down_projection_with_k_slices(hx, ksplit, monkeypatch):
+    """The FFN down projection with large tiles and K = 4096 cut into 2 or 4 slices (fp32 partial sums, second
+    pass), forced on, forced off, and as the launcher chooses (600 rows: slices; 1400 rows: none)."""
+    from paper_2602_01345_amd import Nova
+    if ksplit is not None:
+        monkeypatch.setenv("NOVA_GEMM_KSPLIT", ksplit)
+        monkeypatch.setattr(hx, "_NOVA", Nova(0))
+    _say(f"block bf16 C=1024 F=4096, K slices of the down projection: {ksplit}")
+    for k in (300, 700):
+        wl = _custom("bf16", B=2, grid=28, prev=20, P=500, C=1024, heads=8)
+        errs = hx.check_block(hx.make_host_block(wl, 0, k=k), hx.BF16_TOL)
+        _say(f"   M={2 * k}: errors {errs}")
+
+
 def test_step_with_look_ahead_selection_equals_the_sequential_step(hx):
     """run_step enqueues every block's entropy + selection one block ahead on a second stream; the outputs must
     be those of the plain sequence, bit for bit, also when the step is repeated."""
