@@ -571,13 +571,17 @@ constexpr double kFixed = 8e-6;          // per round of workgroups: launch ramp
 // candidate's sustained rate plus the fixed time.  A projection done by one launch of a single round that fills
 // only a fraction f of the CUs is shorter (the busy CUs share L2 and memory with fewer others): taken as
 // max(0.85, 1.1 f) of a whole round (`alone`).  Measured over the 32 blocks of the largest workload this helps the
-// K = 2048 projections; for the parts of a two-launch plan and for K = 8192 it misleads and is not applied.
+// K = 2048 projections; for the parts of a two-launch plan it misleads and is not applied.  K = 8192 has its own fit.
 double model_time(const Candidate& c, double slots, int M, int Nout, int K, bool alone = false) {
   const double tiles = (double)((M + c.bm - 1) / c.bm) * ((Nout + c.bn - 1) / c.bn);
   const double t_tile = 2.0 * c.bm * c.bn * K / c.rate;
   if (alone && K < 4096 && tiles < slots)   // a whole projection that fills only a fraction of the CUs
     return t_tile * std::max(0.85, std::min(1.0, 1.1 * tiles / slots)) + kFixed;
-  return std::ceil(tiles / slots) * (t_tile + kFixed);
+  // K = 8192 (the FFN down projection), one partly filled round: measured 99 ... 131 us for 80 ... 256 tiles of
+  // 256 x 128 and 70 ... 79 us for 144 ... 256 tiles of 128 x 128, i.e. 0.8 of the fit above at a full round and
+  // a weak dependence on the fill
+  if (K >= 4096 && tiles < slots) return (t_tile + kFixed) * 0.8 * (0.65 + 0.35 * tiles / slots);
+  return std::ceil(tiles / slots) * (t_tile + kFixed) * (K >= 4096 ? 0.8 : 1.0);
 }
 
 int pick_cfg(const nova_ctx* ctx, int M, int Nout, int K, double* t_out = nullptr, bool alone = true) {
