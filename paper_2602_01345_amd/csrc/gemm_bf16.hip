@@ -548,7 +548,7 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float* __restric
 //   1: 256x256x64, 8 waves of 128x64, 2 stages
 //   2: 256x128x64, 8 waves of 64x64, 3 stages
 //   3: 64x32x64, 2 waves of 32x32, 6 stages, staggered K walk          (M <= 64)
-//   4: 128x32x64, 4 waves of 32x32, 4 stages, staggered K walk         (M <= 512)
+//   4: 128x32x64, 4 waves of 32x32, 4 stages, staggered K walk         (M <= 256; M <= 512 for a narrow output and short K)
 //   5: 128x128x64, 4 waves, 3 stages, one workgroup per CU
 //   6: 256x256x32, 8 waves of 128x64, 3 stages
 // Without a forced choice the launcher prices the candidates 2, 5 and 6 with a small model fitted
@@ -584,12 +584,18 @@ double model_time(const Candidate& c, double slots, int M, int Nout, int K, bool
   return std::ceil(tiles / slots) * (t_tile + kFixed) * (K >= 4096 ? 0.8 : 1.0);
 }
 
+// Whether M rows of this projection go to the narrow-tile kernels (see pick_cfg).
+bool narrow_tiles(int M, int Nout, int K) { return M <= 256 || (M <= 512 && Nout < 4096 && K < 4096); }
+
 int pick_cfg(const nova_ctx* ctx, int M, int Nout, int K, double* t_out = nullptr, bool alone = true) {
   if (ctx && ctx->gemm_cfg >= 0 && ctx->gemm_cfg < kNumCfgs) return ctx->gemm_cfg;
   // few rows (the early, small scales): the weights are streamed once and the output has too few
   // large tiles to occupy the CUs, so narrow tiles spread the weight stream over many workgroups
+  // (from 257 rows on only for a narrow output with a short K, the attention output projection: measured at 288 ...
+  // 512 rows, 128 x 32 tiles against 128 x 128: QKV 32-35 / 27 us, FFN1 32-39 / 25-27 us, FFN2 45-49 / 28-34 us
+  // (the latter with K slices), O-proj 17-19 / 23 us)
   if (M <= 64) return 3;
-  if (M <= 512) return 4;
+  if (narrow_tiles(M, Nout, K)) return 4;
   const double slots = ctx ? ctx->num_cus : 256;
   int best = 2;
   double best_t = 1e30;
@@ -613,7 +619,7 @@ Plan plan_rows(const nova_ctx* ctx, int mode, int M, int Nout, int K) {
   double t_single = 1e30;
   p.n = 1; p.m_base[0] = 0; p.m_end[0] = M; p.cfg[0] = pick_cfg(ctx, M, Nout, K, &t_single);
   const bool forced = ctx && ctx->gemm_cfg >= 0 && ctx->gemm_cfg < kNumCfgs;
-  if (forced || mode == EPI_ENTROPY || M <= 512 || (ctx && ctx->gemm_parts == 0)) return p;
+  if (forced || mode == EPI_ENTROPY || M <= 512 || (ctx && ctx->gemm_parts == 0)) return p;   // one launch
   const int slots = ctx ? ctx->num_cus : 256;
   double best = t_single * 0.97;                          // a second launch has to pay for itself
   for (const Candidate& c : kCands) {
@@ -621,7 +627,7 @@ Plan plan_rows(const nova_ctx* ctx, int mode, int M, int Nout, int K) {
       const int m1 = rows * c.bm;
       double t_rest = 0.0;
       const int cfg_rest = pick_cfg(ctx, M - m1, Nout, K, &t_rest, false);
-      if (M - m1 <= 512) {
+      if (narrow_tiles(M - m1, Nout, K)) {
         // the narrow-tile kernels stream the weights once: measured 16 / 21 / 35 us for <= 128 / 256 / 512 rows of
         // a 2048 x 8192 projection, in proportion to the weight bytes, never under 15 us
         const int mr = M - m1;
