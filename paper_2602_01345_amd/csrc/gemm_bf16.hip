@@ -549,7 +549,8 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float* __restric
 //   2: 256x128x64, 8 waves of 64x64, 3 stages
 //   3: 64x32x64, 2 waves of 32x32, 6 stages, staggered K walk          (M <= 64)
 //   4: 128x32x64, 4 waves of 32x32, 4 stages, staggered K walk         (M <= 256; M <= 512 for a narrow output and short K)
-//   5: 128x128x64, 4 waves, 3 stages, one workgroup per CU
+//   5: 128x128x64, 8 waves of 64x32, 3 stages, one workgroup per CU (two waves per SIMD hide the LDS waits that
+//      four waves of 64x64 expose: 3-10 % faster at every shape measured)
 //   6: 256x256x32, 8 waves of 128x64, 3 stages
 // Without a forced choice the launcher prices the candidates 2, 5 and 6 with a small model fitted
 // to measurements on MI355X (M = 1.6k..4.9k, N and K = 2k..8k): a launch takes
@@ -663,7 +664,7 @@ hipError_t launch_part(hipStream_t st, int cfg, const bf16_t* A, const bf16_t* W
       if ((ks == 2 || ks == 4) && K % (ks * bk) == 0 && K / (ks * bk) >= 16) {
         hipError_t e;
         if (cfg == 2) e = launch_cfg<256, 128, 4, 2, 64, 3, false, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, 0, ks);
-        else if (cfg == 5) e = launch_cfg<128, 128, 2, 2, 64, 3, false, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, 0, ks);
+        else if (cfg == 5) e = launch_cfg<128, 128, 2, 4, 64, 3, false, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, 0, ks);
         else e = launch_cfg<256, 256, 2, 4, 32, 3, false, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, 0, ks);
         if (e != hipSuccess) return e;
         const int64_t nvec = (int64_t)(M - m_base) * (Nout / 8);
@@ -693,7 +694,7 @@ hipError_t launch_part(hipStream_t st, int cfg, const bf16_t* A, const bf16_t* W
     case 1: return launch_cfg<256, 256, 2, 4, 64, 2, false, MODE>(st, A, W, m_base, M, Nout, K, ep, slots);
     case 3: return launch_cfg<64, 32, 2, 1, 64, 6, true, MODE>(st, A, W, m_base, M, Nout, K, ep, slots);
     case 4: return launch_cfg<128, 32, 4, 1, 64, 4, true, MODE>(st, A, W, m_base, M, Nout, K, ep, slots);
-    case 5: return launch_cfg<128, 128, 2, 2, 64, 3, false, MODE>(st, A, W, m_base, M, Nout, K, ep, slots);
+    case 5: return launch_cfg<128, 128, 2, 4, 64, 3, false, MODE>(st, A, W, m_base, M, Nout, K, ep, slots);
     case 6: return launch_cfg<256, 256, 2, 4, 32, 3, false, MODE>(st, A, W, m_base, M, Nout, K, ep, slots);
     default: return launch_cfg<256, 128, 4, 2, 64, 3, false, MODE>(st, A, W, m_base, M, Nout, K, ep, slots);
   }
