@@ -405,25 +405,26 @@ def main():
         torch.cuda.synchronize()
         hbm["layer_ratio"] = {"us_per_launch": round(e0.elapsed_time(e1) * 1e3 / len(blocks), 2), "bound": "latency"}
 
-        # entropy straight from a linear head of the workload's width: logits never reach HBM
-        hh = torch.randn((wl.B, scale.N, wl.C), generator=gen, device="cuda").to(dtype)
-        hw = (torch.randn((wl.V, wl.C), generator=gen, device="cuda") * 0.02).to(dtype)
-        hH = torch.empty((wl.B, scale.N), dtype=torch.float32, device="cuda")
-        hws = torch.empty(nova.head_entropy_workspace_bytes(scale.N, wl.B, wl.V), dtype=torch.uint8, device="cuda")
-        reps = 8
-        run_head = lambda: [nova.head_entropy(hh, hw, None, hH, hws) for _ in range(reps)]
-        run_head()
-        torch.cuda.synchronize()
-        e0.record()
-        run_head()
-        e1.record()
-        torch.cuda.synchronize()
-        hus = e0.elapsed_time(e1) * 1e3 / reps
-        hfl = 2.0 * wl.B * scale.N * wl.C * wl.V
-        hbm["head_entropy"] = {"us_per_launch": round(hus, 2), "TFLOP/s": round(hfl / (hus * 1e-6) / 1e12, 1),
-                               "frac_mfma_peak": round(hfl / (hus * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-                               "bound": "mfma", "logits_bytes_not_written": wl.B * scale.N * wl.V * 2}
-        del hh, hw, hH, hws
+        # entropy straight from a linear head of the workload's width: logits never reach HBM (bf16 kernel only)
+        if dtype == torch.bfloat16:
+            hh = torch.randn((wl.B, scale.N, wl.C), generator=gen, device="cuda").to(dtype)
+            hw = (torch.randn((wl.V, wl.C), generator=gen, device="cuda") * 0.02).to(dtype)
+            hH = torch.empty((wl.B, scale.N), dtype=torch.float32, device="cuda")
+            hws = torch.empty(nova.head_entropy_workspace_bytes(scale.N, wl.B, wl.V), dtype=torch.uint8, device="cuda")
+            reps = 8
+            run_head = lambda: [nova.head_entropy(hh, hw, None, hH, hws) for _ in range(reps)]
+            run_head()
+            torch.cuda.synchronize()
+            e0.record()
+            run_head()
+            e1.record()
+            torch.cuda.synchronize()
+            hus = e0.elapsed_time(e1) * 1e3 / reps
+            hfl = 2.0 * wl.B * scale.N * wl.C * wl.V
+            hbm["head_entropy"] = {"us_per_launch": round(hus, 2), "TFLOP/s": round(hfl / (hus * 1e-6) / 1e12, 1),
+                                   "frac_mfma_peak": round(hfl / (hus * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                                   "bound": "mfma", "logits_bytes_not_written": wl.B * scale.N * wl.V * 2}
+            del hh, hw, hH, hws
 
     # what the chip sustains for plain kernels (published peaks: HBM 8 TB/s, dense bf16 MFMA 2.5 PFLOP/s)
     peaks = {}
