@@ -46,16 +46,17 @@ struct EpiParams {
 // native reciprocal and exp2 units instead of the branchy library erff: this runs once per output
 // element of the FFN up-projection.
 __device__ __forceinline__ float gelu_erf(float v) {
-  const float x = fabsf(v) * 0.70710678118654752f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
-  float poly = fmaf(1.061405429f, t, -1.453152027f);
-  poly = fmaf(poly, t, 1.421413741f);
-  poly = fmaf(poly, t, -0.284496736f);
-  poly = fmaf(poly, t, 0.254829592f);
+  // GELU(v) = v Phi(v) = max(v, 0) - |v| h,  h = erfc(|v| / sqrt 2) / 2 = (poly(t) / 2) e^(-v^2 / 2),
+  // t = 1 / (1 + p |v| / sqrt 2): the 1/2 and the 1/sqrt 2 are folded into the constants
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752f, fabsf(v), 1.0f));
+  float poly = fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);
+  poly = fmaf(poly, t, 0.5f * 1.421413741f);
+  poly = fmaf(poly, t, 0.5f * -0.284496736f);
+  poly = fmaf(poly, t, 0.5f * 0.254829592f);
   poly *= t;
-  const float e = __builtin_amdgcn_exp2f(-x * x * 1.4426950408889634f);
-  const float erf_abs = fmaf(-poly, e, 1.0f);               // erf(|v| / sqrt 2)
-  return 0.5f * v * (1.0f + copysignf(erf_abs, v));
+  const float w = v * 0.84932180028801904f;                 // sqrt(log2(e) / 2): e^(-v^2/2) = 2^(-w^2)
+  const float h = poly * __builtin_amdgcn_exp2f(-w * w);
+  return fmaxf(v, 0.0f) - fabsf(v) * h;
 }
 
 // tanh-form GELU 0.5 v (1 + tanh(z)), z = sqrt(2/pi) (v + 0.044715 v^3), written as v / (1 + e^(-2z)).
