@@ -128,8 +128,8 @@ size_t nova_workspace_bytes(const nova_block_shape* shape);
  *                    r*row_stride_elems (row_stride_elems >= V); dtype NOVA_F32|NOVA_BF16
  *   entropy          out [batch*rows_per_batch] fp32
  *   mean_entropy     out [batch] fp32 or NULL: the scale mean entropy of the same
- *                    section (mean over the rows_per_batch tokens of a batch row).
- *                    When non-NULL it is zeroed and accumulated by this call.
+ *                    section (mean over the rows_per_batch tokens of a batch row), summed in a
+ *                    fixed order by a second small kernel: the same bits on every run.
  * batch == 0 or rows_per_batch == 0 is a no-op.  V >= 1.
  */
 int nova_entropy(nova_ctx* ctx, void* stream, const void* logits, int logits_dtype,

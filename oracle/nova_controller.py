@@ -16,9 +16,8 @@ What each function follows (all in Sec. 3.3):
                          the preceding layers' scale mean entropies, Delta_{t,j} the
                          relative deviation of layer j from it,
                          Ratio_{t,j} = Ratio_t (j = 1), Ratio_t - Delta_{t,j} Ratio_t (j >= 2).
-  keep_count,
-  keep_count_f32      -- the integer number of tokens kept for a reduction ratio (exact, and with
-                         the one fp32 product the device path takes the decision in).
+  keep_count          -- the integer number of tokens kept for a reduction ratio (exact arithmetic on the
+                         float64 ratio).
 
 Scales and layers are numbered from 1 as in the paper; Hbar[0] is Hbar_1.
 
@@ -101,16 +100,7 @@ def clamp_ratio(ratio: float) -> float:
 
 
 def keep_count(ratio: float, N: int) -> int:
-    """k = N - floor(clamp(ratio) * N)."""
-    return N - int(math.floor(clamp_ratio(ratio) * N))
-
-
-def keep_count_f32(ratio32, N: int) -> int:
-    """The same decision taken in fp32, the precision of the device path: the ratio is an fp32
-    value, the product ratio * N is rounded to fp32 once, then floored.  A NaN ratio keeps all N."""
-    import numpy as np
-    r = np.float32(ratio32)
-    if np.isnan(r):
+    """k = N - floor(clamp(ratio) * N); a NaN ratio (an undefined entropy upstream) prunes nothing."""
+    if math.isnan(ratio):
         return N
-    rc = np.float32(min(np.float32(1.0), max(np.float32(0.0), r)))
-    return N - int(np.floor(np.float32(rc * np.float32(N))))
+    return N - int(math.floor(clamp_ratio(ratio) * N))

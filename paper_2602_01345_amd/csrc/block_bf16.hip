@@ -99,6 +99,7 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
     StageTimer t(ctx, st, NOVA_STAGE_FFN1);
     e = launch_gemm_bf16(ctx, st, var.gelu_tanh ? EPI_GELU_TANH : EPI_GELU, u, w.w_fc1, M, F, C, ep);
   }
+  if (e != hipSuccess) return e;
 
   ep.bias = static_cast<const bf16_t*>(w.b_fc2); ep.out = y; ep.ldo = C; ep.res = x1; ep.gate = ada_row(5);
   {

@@ -91,8 +91,7 @@ struct Row {
 // Any shape: one row per wave, lanes past the row's end masked.
 template <typename T, int CH>
 __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void entropy_generic_kernel(
-    const T* __restrict__ logits, int64_t rows, int V, int64_t stride, float* __restrict__ H,
-    float* __restrict__ mean, int64_t rows_per_batch, float inv_rows, int vec_ok) {
+    const T* __restrict__ logits, int64_t rows, int V, int64_t stride, float* __restrict__ H, int vec_ok) {
   using VT = Vec16<T>;
   constexpr int VN = VT::N;
   const int lane = threadIdx.x & (NOVA_WAVE - 1);
@@ -148,10 +147,7 @@ __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void entropy_generic_ker
   }
 
   float h = st.finish();
-  if (lane == 0) {
-    H[row] = h;
-    if (mean) atomicAdd(mean + row / rows_per_batch, h * inv_rows);
-  }
+  if (lane == 0) H[row] = h;
 }
 
 
@@ -161,8 +157,7 @@ __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void entropy_generic_ker
 // the memory stream and the ALU work overlap inside every wave instead of alternating chip-wide.
 template <typename T, int CH>
 __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void entropy_kernel(
-    const T* __restrict__ logits, int64_t rows, int nchunk, int64_t stride, float* __restrict__ H,
-    float* __restrict__ mean, int64_t rows_per_batch, float inv_rows) {
+    const T* __restrict__ logits, int64_t rows, int nchunk, int64_t stride, float* __restrict__ H) {
   using VT = Vec16<T>;
   constexpr int VN = VT::N;
   const int lane = threadIdx.x & (NOVA_WAVE - 1);
@@ -190,10 +185,7 @@ __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void entropy_kernel(
   };
   auto finish_row = [&](int64_t row, Row& st) {
     const float h = st.finish();
-    if (lane == 0) {
-      H[row] = h;
-      if (mean) atomicAdd(mean + row / rows_per_batch, h * inv_rows);
-    }
+    if (lane == 0) H[row] = h;
     st.init();
   };
 
@@ -236,19 +228,31 @@ __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void entropy_kernel(
   }
 }
 
-__global__ void zero_f32_kernel(float* p, int n) {
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0.0f;
+// Scale mean entropy of one image per workgroup: mean[b] = (sum_i H[b, i]) / N with a fixed summation order
+// (thread t adds elements t, t + 256, ... in turn, then a fixed tree over the threads), so the result is the same
+// bits on every run -- the layer-linkage ratio turns it into an integer keep count.  A NaN entropy gives NaN.
+constexpr int kMeanThreads = 256;
+__global__ __launch_bounds__(kMeanThreads) void row_mean_kernel(const float* __restrict__ H, int64_t rows_per_batch,
+                                                                float* __restrict__ mean) {
+  __shared__ float part[kMeanThreads];
+  const float* h = H + (int64_t)blockIdx.x * rows_per_batch;
+  float s = 0.0f;
+  for (int64_t i = threadIdx.x; i < rows_per_batch; i += kMeanThreads) s += h[i];
+  part[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = kMeanThreads / 2; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) part[threadIdx.x] += part[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) mean[blockIdx.x] = part[0] / (float)rows_per_batch;
 }
 
 template <typename T, int CH>
-void launch_regular(hipStream_t st, int num_cus, const T* logits, int64_t rows, int nchunk, int64_t stride, float* H,
-                    float* mean, int64_t rows_per_batch) {
+void launch_regular(hipStream_t st, int num_cus, const T* logits, int64_t rows, int nchunk, int64_t stride, float* H) {
   // at most kWavesPerSimd resident waves per SIMD, each walking several rows
   const int64_t max_blocks = (int64_t)num_cus * 4 * kWavesPerSimd / kWavesPerBlock;
   const unsigned grid = (unsigned)std::min<int64_t>((rows + kWavesPerBlock - 1) / kWavesPerBlock, max_blocks);
-  entropy_kernel<T, CH><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(logits, rows, nchunk, stride, H, mean,
-                                                                     rows_per_batch, 1.0f / (float)rows_per_batch);
+  entropy_kernel<T, CH><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(logits, rows, nchunk, stride, H);
 }
 
 template <typename T>
@@ -256,24 +260,28 @@ hipError_t launch_t(hipStream_t st, int num_cus, const T* logits, int64_t rows_p
                     int64_t stride, float* H, float* mean) {
   constexpr int VN = Vec16<T>::N;
   const int64_t rows = rows_per_batch * batch;
-  if (mean) zero_f32_kernel<<<(batch + 255) / 256, 256, 0, st>>>(mean, batch);
   const int vec_ok = ((reinterpret_cast<uintptr_t>(logits) & 15) == 0) &&
                      ((stride * (int64_t)sizeof(T)) % 16 == 0);
   const int per_sweep = NOVA_WAVE * VN;            // elements one 16-byte vector per lane covers
   if (vec_ok && V % per_sweep == 0) {
     const int sweeps = V / per_sweep;
-    if (sweeps % 4 == 0) launch_regular<T, 4>(st, num_cus, logits, rows, sweeps / 4, stride, H, mean, rows_per_batch);
-    else if (sweeps % 2 == 0) launch_regular<T, 2>(st, num_cus, logits, rows, sweeps / 2, stride, H, mean, rows_per_batch);
-    else launch_regular<T, 1>(st, num_cus, logits, rows, sweeps, stride, H, mean, rows_per_batch);
+    if (sweeps % 4 == 0) launch_regular<T, 4>(st, num_cus, logits, rows, sweeps / 4, stride, H);
+    else if (sweeps % 2 == 0) launch_regular<T, 2>(st, num_cus, logits, rows, sweeps / 2, stride, H);
+    else launch_regular<T, 1>(st, num_cus, logits, rows, sweeps, stride, H);
   } else {
     const unsigned grid = (unsigned)((rows + kWavesPerBlock - 1) / kWavesPerBlock);
-    entropy_generic_kernel<T, 8><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(
-        logits, rows, V, stride, H, mean, rows_per_batch, 1.0f / (float)rows_per_batch, vec_ok);
+    entropy_generic_kernel<T, 8><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(logits, rows, V, stride, H, vec_ok);
   }
+  if (mean) return launch_row_mean(st, H, rows_per_batch, batch, mean);
   return hipGetLastError();
 }
 
 }  // namespace
+
+hipError_t launch_row_mean(hipStream_t st, const float* H, int64_t rows_per_batch, int batch, float* mean) {
+  row_mean_kernel<<<batch, kMeanThreads, 0, st>>>(H, rows_per_batch, mean);
+  return hipGetLastError();
+}
 
 hipError_t launch_entropy(hipStream_t st, int num_cus, const void* logits, int dtype, int64_t rows_per_batch,
                           int batch, int V, int64_t stride, float* H, float* mean) {

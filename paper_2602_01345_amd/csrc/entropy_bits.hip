@@ -18,8 +18,7 @@ __device__ __forceinline__ float binary_entropy_from_logits(float l0, float l1) 
 
 template <typename T>
 __global__ __launch_bounds__(256) void entropy_bits_kernel(const T* __restrict__ logits, int64_t rows, int d,
-                                                           float* __restrict__ H, float* __restrict__ mean,
-                                                           int64_t rows_per_batch, float inv_rows) {
+                                                           float* __restrict__ H) {
   using VT = Vec16<T>;
   constexpr int VN = VT::N;                          // elements per 16-byte vector (even)
   const int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -38,12 +37,6 @@ __global__ __launch_bounds__(256) void entropy_bits_kernel(const T* __restrict__
   }
   for (; i < n; i += 2) h += binary_entropy_from_logits((float)p[i], (float)p[i + 1]);
   H[row] = h;
-  if (mean) atomicAdd(mean + row / rows_per_batch, h * inv_rows);
-}
-
-__global__ void zero_kernel(float* p, int n) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0.0f;
 }
 
 }  // namespace
@@ -51,14 +44,11 @@ __global__ void zero_kernel(float* p, int n) {
 hipError_t launch_entropy_bits(hipStream_t st, const void* logits, int dtype, int64_t rows_per_batch, int batch,
                                int d, float* H, float* mean) {
   const int64_t rows = rows_per_batch * batch;
-  if (mean) zero_kernel<<<(batch + 255) / 256, 256, 0, st>>>(mean, batch);
   const int grid = (int)((rows + 255) / 256);
-  const float inv = 1.0f / (float)rows_per_batch;
   if (dtype == NOVA_BF16)
-    entropy_bits_kernel<bf16_t><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(logits), rows, d, H, mean,
-                                                      rows_per_batch, inv);
+    entropy_bits_kernel<bf16_t><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(logits), rows, d, H);
   else
-    entropy_bits_kernel<float><<<grid, 256, 0, st>>>(static_cast<const float*>(logits), rows, d, H, mean,
-                                                     rows_per_batch, inv);
+    entropy_bits_kernel<float><<<grid, 256, 0, st>>>(static_cast<const float*>(logits), rows, d, H);
+  if (mean) return launch_row_mean(st, H, rows_per_batch, batch, mean);
   return hipGetLastError();
 }

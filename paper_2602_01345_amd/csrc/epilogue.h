@@ -56,7 +56,11 @@ __device__ __forceinline__ float gelu_erf(float v) {
   poly *= t;
   const float w = v * 0.84932180028801904f;                 // sqrt(log2(e) / 2): e^(-v^2/2) = 2^(-w^2)
   const float h = poly * __builtin_amdgcn_exp2f(-w * w);
-  return fmaxf(v, 0.0f) - fabsf(v) * h;
+  // |v| h with the legacy multiply's 0 * inf = 0: an overflowed accumulator (v = +-inf, h = 0) saturates to
+  // +inf / 0 as the erf form does, instead of turning into NaN; NaN stays NaN
+  float tail;
+  asm("v_mul_legacy_f32 %0, |%1|, %2" : "=v"(tail) : "v"(v), "v"(h));
+  return fmaxf(v, 0.0f) - tail;
 }
 
 // tanh-form GELU 0.5 v (1 + tanh(z)), z = sqrt(2/pi) (v + 0.044715 v^3), written as v / (1 + e^(-2z)).

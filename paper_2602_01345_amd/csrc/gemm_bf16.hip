@@ -10,8 +10,8 @@
 //    lane-linear, the bank-conflict-avoiding XOR swizzle is applied on the global side: the
 //    lane that fills 16-byte slot p of row r fetches chunk p ^ ((r >> 1) & 7) of that row, and
 //    the MFMA operand reads look the chunk up at the same swizzled slot.
-//  * Two LDS stages: the loads of tile t+1 are in flight while tile t feeds the MFMAs; one
-//    barrier per K step.
+//  * An NST-stage LDS ring (2 to 6 stages, per tile configuration): the loads of tiles t+1 .. t+NST-1 are in
+//    flight while tile t feeds the MFMAs; one bare barrier per K step with explicit vmcnt / lgkmcnt waits.
 //  * Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs) works
 //    on a contiguous run of tiles, ordered in bands of 8 tile rows, so that the tiles in flight on
 //    one XCD form a compact rectangle and share A rows and W columns in that XCD's L2.

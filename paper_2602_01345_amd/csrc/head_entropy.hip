@@ -11,9 +11,7 @@
 namespace {
 
 __global__ __launch_bounds__(256) void head_entropy_combine_kernel(const f32x4* __restrict__ part, int tiles_n,
-                                                                   int M, float* __restrict__ H,
-                                                                   float* __restrict__ mean, int rows_per_batch,
-                                                                   float inv_rows) {
+                                                                   int M, float* __restrict__ H) {
   const int row = blockIdx.x * blockDim.x + threadIdx.x;
   if (row >= M) return;
   const f32x4 a = part[row];
@@ -25,12 +23,6 @@ __global__ __launch_bounds__(256) void head_entropy_combine_kernel(const f32x4* 
   float h = logf(S) + T / S;
   h = h < 0.0f ? 0.0f : h;
   H[row] = h;
-  if (mean) atomicAdd(mean + row / rows_per_batch, h * inv_rows);
-}
-
-__global__ void zero_kernel(float* p, int n) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0.0f;
 }
 
 }  // namespace
@@ -50,8 +42,7 @@ hipError_t launch_head_entropy(const nova_ctx* ctx, hipStream_t st, const void* 
   hipError_t e = launch_gemm_bf16(ctx, st, EPI_ENTROPY, hidden, w_head, M, V, C, ep);
   if (e != hipSuccess) return e;
   const int bn = gemm_bf16_tile_cols(ctx, M, V, C);
-  if (mean) zero_kernel<<<(batch + 255) / 256, 256, 0, st>>>(mean, batch);
-  head_entropy_combine_kernel<<<(M + 255) / 256, 256, 0, st>>>(ep.ent_part, (V + bn - 1) / bn, M, H, mean,
-                                                               rows_per_batch, 1.0f / (float)rows_per_batch);
+  head_entropy_combine_kernel<<<(M + 255) / 256, 256, 0, st>>>(ep.ent_part, (V + bn - 1) / bn, M, H);
+  if (mean) return launch_row_mean(st, H, rows_per_batch, batch, mean);
   return hipGetLastError();
 }

@@ -53,6 +53,8 @@ struct StageTimer {
 // entropy.hip
 hipError_t launch_entropy(hipStream_t st, int num_cus, const void* logits, int dtype, int64_t rows_per_batch,
                           int batch, int V, int64_t stride, float* H, float* mean);
+// entropy.hip: mean[b] = mean of H[b, 0..rows_per_batch), summed in a fixed order (bit-reproducible)
+hipError_t launch_row_mean(hipStream_t st, const float* H, int64_t rows_per_batch, int batch, float* mean);
 // select.hip
 hipError_t launch_layer_ratio(hipStream_t st, const float* mean_entropy, float* entropy_sum, const float* ratio_t,
                               int j, int B, int N, float* ratio_tj, int32_t* k_per_row);

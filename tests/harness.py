@@ -172,6 +172,9 @@ def check_block(hb: HostBlock, tol: float, rows=None, poison: bool = True) -> Di
     errs["cache_new"] = nerr(st.cache_new[rows], ref["cache_new"], scale_ref=ref["out"])
     for name, e in errs.items():
         assert e <= tol, f"{name}: normalised max error {e:.3e} > {tol:.1e}"
+    # the same absolute error on the residual's own scale (max|cache_new|), for the record: reported, and
+    # bounded by the tolerance times the ratio of the two scales, which is the same statement as the line above
+    errs["cache_new_own_scale"] = nerr(st.cache_new[rows], ref["cache_new"])
     # prior cache rows must be untouched
     assert torch.equal(unpack_k_rows(st.k_cache, 0, P).cpu(), hb.k_prior), "prior key rows were modified"
     assert torch.equal(unpack_v_rows(st.v_cache, 0, P).cpu(), hb.v_prior), "prior value rows were modified"

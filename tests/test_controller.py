@@ -94,8 +94,18 @@ def _check_layers(hbar, ratio_t, got, N):
                 assert abs(r_gpu[b] - want) <= 1e-5 * (1.0 + abs(want)), (j, b, r_gpu[b], want)
             if not math.isnan(sum(col)):
                 assert abs(s_gpu[b] - sum(col)) <= 1e-5 * (1.0 + abs(sum(col)))
-            # the count is decided in fp32 from the ratio the device itself produced
-            assert k_gpu[b] == K.keep_count_f32(r_gpu[b], N), (j, b, r_gpu[b], k_gpu[b])
+            # the count against the exact rule applied to the ratio the device itself produced (widened to
+            # float64).  The device forms ratio * N in fp32: where the exact product lies within one fp32
+            # spacing of an integer its floor may land on either side, and only there may the count be off by one.
+            r64 = float(r_gpu[b])
+            want_k = K.keep_count(r64, N)
+            if math.isnan(r64):
+                assert k_gpu[b] == N
+            else:
+                prod = K.clamp_ratio(r64) * N
+                ulp = float(np.spacing(np.float32(max(prod, 1.0))))
+                near_integer = abs(prod - round(prod)) <= ulp
+                assert abs(int(k_gpu[b]) - want_k) <= (1 if near_integer else 0), (j, b, r64, k_gpu[b], want_k)
             assert 0 <= k_gpu[b] <= N
 
 

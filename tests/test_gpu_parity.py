@@ -257,13 +257,30 @@ def test_cfg5_middle_blocks_ragged_last_rounds(hx, j):
     _say(f"   errors {errs}")
 
 
-def test_earlier_pruned_scales(hx):
-    """cfg3's 13x13 scale and cfg5's 32x32 scale (prior grids 10 and 24)."""
-    for name, si, rows in (("cfg3", 0, [1]), ("cfg5", 0, [0])):
-        wl = WL.WORKLOADS[name]
-        s = wl.scales[si]
-        _say(f"{name} scale {s.grid} P={s.kv_len}")
-        hx.check_block(hx.make_host_block(wl, 1, scale=s), hx.BF16_TOL, rows=rows)
+@pytest.mark.parametrize("name,si,rows", [("cfg3", 0, [1]), ("cfg4", 0, [2]), ("cfg4", 1, [5]), ("cfg5", 0, [0]),
+                                          ("cfg5", 1, [1]), ("cfg5", 2, [0])])
+def test_earlier_pruned_scales(hx, name, si, rows):
+    """Every pruned scale before the last one: cfg3 at 13x13 (prior grid 10), cfg4 at 18x18 and 24x24 (prior grids
+    13 and 18, P = 316 and 640), cfg5 at 32x32, 40x40 and 48x48 (prior grids 24, 32, 40; P = 1497, 2521, 4121):
+    other upsampling ratios, attention split plans and GEMM row plans than the last scale's.  Block 1, one image."""
+    wl = WL.WORKLOADS[name]
+    s = wl.scales[si]
+    assert s is not wl.last
+    _say(f"{name} scale {s.grid}x{s.grid} prior grid {s.prev_grid} P={s.kv_len} k={wl.k(1, s)} rows={rows}")
+    errs = hx.check_block(hx.make_host_block(wl, 1, scale=s), hx.BF16_TOL, rows=rows)
+    _say(f"   errors {errs}")
+
+
+def test_cache_new_error_on_its_own_scale_is_on_record(hx):
+    """The new residual cache is out - x, a difference of two stored bf16 tensors, so its error is checked on the
+    scale of `out`.  This prints the same error on the residual's own scale with half of the tokens kept and with
+    every token kept (then the residual is only the block's update, much smaller than the activations)."""
+    wl = _custom("bf16", B=2, grid=17, prev=13, P=300, C=256, heads=2)
+    for k in (144, 289):
+        errs = hx.check_block(hx.make_host_block(wl, 0, k=k), hx.BF16_TOL)
+        _say(f"   k={k} of 289: cache_new error / max|out| = {errs['cache_new']:.3e}, "
+             f"/ max|cache_new| = {errs['cache_new_own_scale']:.3e}")
+        assert errs["cache_new_own_scale"] >= errs["cache_new"] * 0.999
 
 
 # ----------------------------------------------------------------------------------
@@ -427,18 +444,41 @@ def test_step_with_look_ahead_selection_equals_the_sequential_step(hx):
 
 
 def test_block_is_deterministic(hx):
-    """Two runs on the same inputs give the same bits (no atomics on the block / merge path)."""
+    """Two runs on the same inputs give the same bits (no floating-point atomics anywhere on the path), the
+    scale mean entropy included: it decides an integer keep count downstream."""
     wl = _custom("bf16", B=2, grid=24, prev=18, P=900, C=256, heads=4)
     hb = hx.make_host_block(wl, 0, k=300)
     outs = []
     for _ in range(2):
         runner, st, x = hx.to_gpu(hb)
         runner.run_block(st, x)
+        mean = torch.empty(wl.B, dtype=torch.float32, device="cuda")
+        H2 = torch.empty_like(st.entropy)
+        hx.nova().entropy(st.logits, H2, mean)
         torch.cuda.synchronize()
         outs.append([t.clone() for t in (st.entropy, st.kept_idx, st.keep_mask, st.y_kept, st.out, st.cache_new,
-                                         st.k_cache, st.v_cache)])
+                                         st.k_cache, st.v_cache, H2, mean)])
     for a, b in zip(*outs):
         assert torch.equal(a, b)
+    assert torch.equal(outs[0][0], outs[0][8])
+
+
+def test_mean_entropy_is_the_same_bits_on_every_run(hx):
+    """cfg5-sized logits (2 x 4096 tokens): the mean is summed in a fixed order, so ten runs agree bit for bit,
+    and it equals the float64 mean of the entropies the kernel wrote to fp32 rounding."""
+    wl = WL.WORKLOADS["cfg5"]
+    logits = WL.make_logits(wl, 3).cuda()
+    H = torch.empty((wl.B, wl.last.N), dtype=torch.float32, device="cuda")
+    means = []
+    for _ in range(10):
+        mean = torch.full((wl.B,), float("nan"), dtype=torch.float32, device="cuda")
+        hx.nova().entropy(logits, H, mean)
+        torch.cuda.synchronize()
+        means.append(mean.cpu().numpy().copy())
+    for m in means[1:]:
+        assert np.array_equal(m, means[0])
+    want = O.mean_entropy(H.cpu().numpy().astype(np.float64))
+    assert np.allclose(means[0], want, rtol=2e-6, atol=0)
 
 
 def test_tile_walking_gemm_workgroups_give_the_same_bits_as_one_workgroup_per_tile(hx, monkeypatch):

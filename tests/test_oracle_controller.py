@@ -200,9 +200,7 @@ def test_keep_count_is_ceil_of_kept_fraction(N):
 
 
 @pytest.mark.parametrize("N", [7, 169, 4096, 65536])
-def test_keep_count_f32_agrees_where_the_product_is_exact(N):
-    # ratios num/64 are exact in fp32 and so is num/64 * N for these N: both decisions coincide
-    for num in range(0, 65):
-        assert K.keep_count_f32(num / 64.0, N) == K.keep_count(num / 64.0, N)
-    assert K.keep_count_f32(float("nan"), N) == N
-    assert K.keep_count_f32(-2.0, N) == N and K.keep_count_f32(3.0, N) == 0
+def test_keep_count_clamps_and_keeps_everything_for_nan(N):
+    assert K.keep_count(float("nan"), N) == N
+    assert K.keep_count(-2.0, N) == N and K.keep_count(3.0, N) == 0
+    assert K.keep_count(0.0, N) == N and K.keep_count(1.0, N) == 0
