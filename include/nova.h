@@ -35,7 +35,8 @@ enum {
   NOVA_ERR_INVALID_ARG = -1, /* null pointer, negative size, k > N, misaligned pointer ...      */
   NOVA_ERR_UNSUPPORTED = -2, /* valid request the kernels do not cover (dtype, head size ...)  */
   NOVA_ERR_WORKSPACE = -3,   /* workspace smaller than nova_workspace_bytes()                   */
-  NOVA_ERR_HIP = -4          /* a HIP runtime call failed (launch error, wrong device ...)      */
+  NOVA_ERR_HIP = -4,         /* a HIP runtime call failed (launch error, wrong device ...)      */
+  NOVA_ERR_STATIC_SCRATCH = -5 /* the request needs more than the static scratch of the allocation-free entry point */
 };
 
 enum { NOVA_F32 = 0, NOVA_BF16 = 1 }; /* storage type of activations / weights / logits */
@@ -166,6 +167,22 @@ size_t nova_head_entropy_workspace_bytes(int64_t rows_per_batch, int batch, int 
 int nova_head_entropy(nova_ctx* ctx, void* stream, const void* hidden, const void* w_head,
                       const void* b_head, int dtype, int64_t rows_per_batch, int batch, int C, int V,
                       float* entropy, float* mean_entropy, void* workspace, size_t workspace_bytes);
+
+/*
+ * nova_head_entropy for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels, with the per-tile entropy
+ * partials in a static device array of NOVA_HEAD_ENTROPY_STATIC_BYTES (4 MiB) that each GPU the library runs
+ * on holds until the process ends (its address on the context's device is resolved by nova_create).  The call
+ * allocates nothing.  It needs 16 bytes per row and per column tile of the GEMM configuration picked for the
+ * shape (256 columns at the large workloads: 2 MiB for 8192 rows and V = 4096); a request that needs more than
+ * the array returns NOVA_ERR_STATIC_SCRATCH and launches nothing.  Results are those of nova_head_entropy, bit for
+ * bit.  All calls on one GPU share the array: calls that overlap on one GPU (two streams, two threads, two contexts)
+ * race; nothing in it has to be cleared between calls (every partial that is read is written first).
+ */
+#define NOVA_HEAD_ENTROPY_STATIC_BYTES ((size_t)4 << 20)
+int nova_head_entropy_static(nova_ctx* ctx, void* stream, const void* hidden, const void* w_head,
+                             const void* b_head, int dtype, int64_t rows_per_batch, int batch, int C, int V,
+                             float* entropy, float* mean_entropy);
 
 /*
  * Entropy-guided token selection (Sec. 3.3, "Dual-Linkage Acceleration", final

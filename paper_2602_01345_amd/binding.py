@@ -114,6 +114,8 @@ def load_library() -> C.CDLL:
     lib.nova_head_entropy_workspace_bytes.restype = C.c_size_t
     lib.nova_head_entropy.argtypes = [vp, vp, vp, vp, vp, i32, i64, i32, i32, i32, vp, vp, vp, C.c_size_t]
     lib.nova_head_entropy.restype = i32
+    lib.nova_head_entropy_static.argtypes = [vp, vp, vp, vp, vp, i32, i64, i32, i32, i32, vp, vp]
+    lib.nova_head_entropy_static.restype = i32
     lib.nova_pruned_block.argtypes = [vp, vp, C.POINTER(_Shape), C.POINTER(_Weights), vp, vp, vp, vp, vp, vp,
                                       C.c_size_t]
     lib.nova_pruned_block_variant.argtypes = [vp, vp, C.POINTER(_Shape), C.POINTER(_Weights), C.POINTER(_Variant),
@@ -269,6 +271,15 @@ class Nova:
                                         _dtype_code(hidden), N, B, Cc, V, _ptr(entropy), _ptr(mean),
                                         _ptr(workspace), workspace.numel() * workspace.element_size())
         self._check(rc, "nova_head_entropy")
+
+    def head_entropy_static(self, hidden: torch.Tensor, w_head: torch.Tensor, b_head: Optional[torch.Tensor],
+                            entropy: torch.Tensor, mean: Optional[torch.Tensor] = None):
+        """nova_head_entropy_static: as head_entropy, the partials in the library's static device scratch."""
+        B, N, Cc = hidden.shape
+        V = w_head.shape[0]
+        rc = self.lib.nova_head_entropy_static(self.ctx, _stream(), _ptr(hidden), _ptr(w_head), _ptr(b_head),
+                                               _dtype_code(hidden), N, B, Cc, V, _ptr(entropy), _ptr(mean))
+        self._check(rc, "nova_head_entropy_static")
 
     # -- nova_select ----------------------------------------------------------------
     def select(self, entropy: torch.Tensor, k: int, kept_idx: torch.Tensor, keep_mask: torch.Tensor,

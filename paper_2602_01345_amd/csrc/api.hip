@@ -74,6 +74,8 @@ int nova_create(nova_ctx** out, int device_id) {
   if (device_id < 0 || device_id >= n) return NOVA_ERR_INVALID_ARG;
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, device_id) != hipSuccess) return NOVA_ERR_HIP;
+  // the allocation-free entry point's scratch is a static device array: resolve its address on this device now
+  if (head_entropy_static_init(device_id) != hipSuccess) return NOVA_ERR_HIP;
   nova_ctx* c = new (std::nothrow) nova_ctx;
   if (!c) return NOVA_ERR_HIP;
   c->device = device_id;
@@ -170,6 +172,7 @@ const char* nova_strerror(int code) {
     case NOVA_ERR_UNSUPPORTED: return "unsupported shape or dtype";
     case NOVA_ERR_WORKSPACE: return "workspace too small or misaligned";
     case NOVA_ERR_HIP: return "HIP runtime error";
+    case NOVA_ERR_STATIC_SCRATCH: return "request exceeds the static scratch of the allocation-free entry point";
     default: return "unknown error code";
   }
 }
@@ -231,6 +234,28 @@ int nova_head_entropy(nova_ctx* ctx, void* stream, const void* hidden, const voi
   if (int rc = set_device(ctx)) return rc;
   hipError_t e = launch_head_entropy(ctx, static_cast<hipStream_t>(stream), hidden, w_head, b_head,
                                      (int)rows_per_batch, batch, C, V, entropy, mean_entropy, workspace);
+  return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
+}
+
+int nova_head_entropy_static(nova_ctx* ctx, void* stream, const void* hidden, const void* w_head,
+                             const void* b_head, int dtype, int64_t rows_per_batch, int batch, int C, int V,
+                             float* entropy, float* mean_entropy) {
+  if (!ctx) return NOVA_ERR_INVALID_ARG;
+  if (dtype != NOVA_BF16) return NOVA_ERR_UNSUPPORTED;
+  if (rows_per_batch < 0 || batch < 0 || V < 1 || C < 1) return NOVA_ERR_INVALID_ARG;
+  if (rows_per_batch == 0 || batch == 0) return NOVA_OK;
+  if (rows_per_batch * batch > ((int64_t)1 << 24)) return NOVA_ERR_UNSUPPORTED;
+  if (C % 64 != 0) return NOVA_ERR_UNSUPPORTED;
+  if (!hidden || !w_head || !entropy) return NOVA_ERR_INVALID_ARG;
+  for (const void* p : {hidden, w_head, b_head})
+    if (reinterpret_cast<uintptr_t>(p) % 16 != 0) return NOVA_ERR_INVALID_ARG;
+  if (head_entropy_partial_bytes(ctx, (int)(rows_per_batch * batch), V, C) > head_entropy_static_capacity())
+    return NOVA_ERR_STATIC_SCRATCH;
+  void* scratch_ptr = head_entropy_static_scratch(ctx->device);     // resolved by nova_create on this device
+  if (!scratch_ptr) return NOVA_ERR_HIP;
+  if (int rc = set_device(ctx)) return rc;
+  hipError_t e = launch_head_entropy(ctx, static_cast<hipStream_t>(stream), hidden, w_head, b_head,
+                                     (int)rows_per_batch, batch, C, V, entropy, mean_entropy, scratch_ptr);
   return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
 }
 

@@ -25,7 +25,44 @@ __global__ __launch_bounds__(256) void head_entropy_combine_kernel(const f32x4* 
   H[row] = h;
 }
 
+// Scratch of the allocation-free entry point (nova_head_entropy_static): the per-tile entropy partials live in
+// this array instead of a caller's workspace.  Every GPU the library runs on holds its own copy at its own
+// address; the array's name is only a host-side handle, the device address comes from hipGetSymbolAddress.
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};       // device address of `scratch` on each device, set by head_entropy_static_init
+
 }  // namespace
+
+hipError_t head_entropy_static_init(int device) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  if (g_scratch_ptr[device]) return hipSuccess;
+  int cur = -1;
+  hipError_t e = hipGetDevice(&cur);
+  if (e != hipSuccess) return e;
+  if (cur != device && (e = hipSetDevice(device)) != hipSuccess) return e;
+  void* p = nullptr;
+  e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+  if (cur != device) (void)hipSetDevice(cur);
+  if (e != hipSuccess) return e;
+  g_scratch_ptr[device] = p;
+  return hipSuccess;
+}
+
+void* head_entropy_static_scratch(int device) {
+  return device >= 0 && device < kMaxDevices ? g_scratch_ptr[device] : nullptr;
+}
+
+size_t head_entropy_static_capacity() { return kStaticScratchBytes; }
+
+// Bytes of partials the launch below really writes for this shape: one 16-byte partial per row and per column
+// tile of the GEMM configuration the launcher picks.
+size_t head_entropy_partial_bytes(const nova_ctx* ctx, int M, int V, int C) {
+  const int bn = gemm_bf16_tile_cols(ctx, M, V, C);
+  return (size_t)((V + bn - 1) / bn) * (size_t)M * sizeof(f32x4);
+}
 
 size_t head_entropy_workspace_bytes(int M, int V) {
   // one 16-byte partial per row and column tile; the narrowest tile configuration has 32 columns

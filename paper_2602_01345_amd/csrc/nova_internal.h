@@ -105,6 +105,12 @@ size_t head_entropy_workspace_bytes(int M, int V);
 hipError_t launch_head_entropy(const nova_ctx* ctx, hipStream_t st, const void* hidden, const void* w_head,
                                const void* b_head, int rows_per_batch, int batch, int C, int V, float* H,
                                float* mean, void* workspace);
+// the allocation-free variant's scratch: a static device array in head_entropy.hip.  _init resolves its address
+// on `device` once (hipGetSymbolAddress with that device current); _scratch returns it (nullptr before _init)
+hipError_t head_entropy_static_init(int device);
+void* head_entropy_static_scratch(int device);
+size_t head_entropy_static_capacity();
+size_t head_entropy_partial_bytes(const nova_ctx* ctx, int M, int V, int C);
 // attention_bf16.hip: attn[B*k, C] = softmax(ln 2 * q K^T) V per head over kv_total cached keys: the query rows
 // arrive multiplied by (score scale * log2 e) -- kAttnLog2e times the scale of the scores -- by whoever wrote
 // them (the projection's epilogue or the unit-length rescaling), so the kernel's scores are in log2 units
