@@ -170,8 +170,16 @@ def _f64(a):
     return None if a is None else np.asarray(a, dtype=np.float64)
 
 
-def pruned_block(x, idx, weights, k_prior, v_prior, heads, gelu_form="erf", qk_scale=None, ada=None, cross=None):
+def pruned_block(x, idx, weights, k_prior, v_prior, heads, gelu_form="erf", qk_scale=None, ada=None, cross=None,
+                 kv_rows=None):
     """One transformer block on the kept tokens only.
+
+    Per-image keep counts (the reduction ratios of Sec. 3.3, "Dual-Linkage Acceleration", are per
+    instance): image b keeps the tokens idx[b, :k_b], where k_b is the number of non-negative entries at
+    the front of idx[b] (the unused tail of a row is -1, as `select` writes it), and attends to its own
+    kv_rows[b] prior rows (all of k_prior[b] when kv_rows is None) plus its own k_b kept rows.  Every image
+    is computed on its own: nothing of one image enters another's result.  Rows past k_b of the three
+    outputs are zero.
 
     Variants (all off by default):
       gelu_form  "erf" | "tanh"
@@ -213,13 +221,18 @@ def pruned_block(x, idx, weights, k_prior, v_prior, heads, gelu_form="erf", qk_s
     y_kept = np.zeros((B, k, C))
     k_new = np.zeros((B, k, C))
     v_new = np.zeros((B, k, C))
+    k_pitch = k
     for b in range(B):
         if ada is None:
             shift1 = scale1 = shift2 = scale2 = 0.0
             gate1 = gate2 = 1.0
         else:
             shift1, scale1, gate1, shift2, scale2, gate2 = ada[b]
-        xs = x[b, idx[b]]                                 # gather kept rows  [k, C]
+        k = _row_count(idx[b])                            # this image's keep count
+        if k == 0:
+            continue
+        Pb = k_prior.shape[1] if kv_rows is None else int(kv_rows[b])
+        xs = x[b, idx[b, :k]]                             # gather kept rows  [k, C]
         u = layer_norm(xs) * (1.0 + scale1) + shift1
         qkv = u @ W["w_qkv"].T + bias("b_qkv")
         q, kk, vv = qkv[:, :C].copy(), qkv[:, C:2 * C].copy(), qkv[:, 2 * C:]
@@ -228,9 +241,9 @@ def pruned_block(x, idx, weights, k_prior, v_prior, heads, gelu_form="erf", qk_s
                 sl = slice(h * dh, (h + 1) * dh)
                 q[:, sl] = unit_rows(q[:, sl])
                 kk[:, sl] = unit_rows(kk[:, sl])
-        k_new[b], v_new[b] = kk, vv
-        Kc = np.concatenate([k_prior[b], kk], axis=0)     # [P + k, C]
-        Vc = np.concatenate([v_prior[b], vv], axis=0)
+        k_new[b, :k], v_new[b, :k] = kk, vv
+        Kc = np.concatenate([k_prior[b, :Pb], kk], axis=0)     # [P + k, C]
+        Vc = np.concatenate([v_prior[b, :Pb], vv], axis=0)
         a = np.zeros((k, C))
         for h in range(heads):
             sl = slice(h * dh, (h + 1) * dh)
@@ -249,8 +262,17 @@ def pruned_block(x, idx, weights, k_prior, v_prior, heads, gelu_form="erf", qk_s
                 ac[:, sl] = softmax((qc[:, sl] @ Kt[:, sl].T) / np.sqrt(dh)) @ Vt[:, sl]
             x1 = x1 + ac @ _f64(cross["w_co"]).T + b_co
         hdn = act((layer_norm(x1) * (1.0 + scale2) + shift2) @ W["w_fc1"].T + bias("b_fc1"))
-        y_kept[b] = x1 + gate2 * (hdn @ W["w_fc2"].T + bias("b_fc2"))
+        y_kept[b, :k] = x1 + gate2 * (hdn @ W["w_fc2"].T + bias("b_fc2"))
+    assert y_kept.shape[1] == k_pitch
     return y_kept, k_new, v_new
+
+
+def _row_count(idx_row) -> int:
+    """Entries of a kept-index row in front of its -1 tail (all of them when there is no tail)."""
+    neg = np.flatnonzero(np.asarray(idx_row) < 0)
+    n = int(neg[0]) if neg.size else len(idx_row)
+    assert np.all(np.asarray(idx_row)[n:] < 0), "a -1 tail must be contiguous"
+    return n
 
 
 # ----------------------------------------------------------------------------
@@ -341,18 +363,20 @@ def merge_cache(x, y_kept, idx, cache_prev, hp, wp, h, w, interp="bilinear"):
     out[b, i]       = y_kept[b, s]               if i == idx[b, s]
                     = x[b, i] + cache_up[b, i]   otherwise
     cache_new[b, i] = out[b, i] - x[b, i]
-    cache_prev may be None when every token is kept.
+    cache_prev may be None when every token is kept.  Per-image keep counts: a row of idx may end in a
+    tail of -1 entries (its image keeps fewer tokens than the row is long); those entries and the rows of
+    y_kept that go with them are ignored.
     """
     x, y_kept = _f64(x), _f64(y_kept)
     idx = np.asarray(idx, dtype=np.int64)
     B, N, C = x.shape
     assert N == h * w
-    k = idx.shape[1]
-    if k < N:
+    counts = [_row_count(idx[b]) for b in range(B)]
+    if min(counts, default=N) < N:
         out = x + UPSAMPLERS[interp](cache_prev, hp, wp, h, w)
     else:
         out = np.zeros_like(x)
     for b in range(B):
-        out[b, idx[b]] = y_kept[b]
+        out[b, idx[b, :counts[b]]] = y_kept[b, :counts[b]]
     cache_new = out - x
     return out, cache_new

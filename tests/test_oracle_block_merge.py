@@ -574,3 +574,81 @@ def test_cross_attention_library_second_opinion_torch_float64(bias, with_others)
         hdn = F.gelu(F.linear(n2, t["w_fc1"], t["b_fc1"]), approximate="tanh" if with_others else "none")
         ref = x1 + m[5] * F.linear(hdn, t["w_fc2"], t["b_fc2"])
         np.testing.assert_allclose(y[b], ref.numpy(), rtol=1e-9, atol=1e-11)
+
+
+# ---- per-image keep counts (the reduction ratios are per instance) ---------------------------------------
+def _ragged_case(rng):
+    B, N, C, P = 3, 7, 8, 4
+    x, W, kp, vp = _rand_block(rng, B=B, N=N, C=C, P=P)
+    counts = [4, 0, 7]                                   # some, none, all
+    kv_rows = [3, 1, 4]                                  # each image's own number of prior rows
+    idx = np.full((B, N), -1, dtype=np.int64)
+    idx[0, :4] = [1, 2, 4, 6]
+    idx[2, :7] = np.arange(7)
+    return x, W, kp, vp, idx, counts, kv_rows
+
+
+def test_per_image_counts_equal_each_image_run_on_its_own():
+    """A batch whose images keep different numbers of tokens and hold different numbers of prior rows: every
+    image's outputs are those of a single-image call with its own trimmed index list and prior rows."""
+    rng = np.random.default_rng(21)
+    x, W, kp, vp, idx, counts, kv_rows = _ragged_case(rng)
+    y, kn, vn = O.pruned_block(x, idx, W, kp, vp, heads=2, kv_rows=kv_rows)
+    assert y.shape == (3, 7, 8)
+    for b, (k, P) in enumerate(zip(counts, kv_rows)):
+        if k:
+            y1, k1, v1 = O.pruned_block(x[b:b + 1], idx[b:b + 1, :k], W, kp[b:b + 1, :P], vp[b:b + 1, :P], heads=2)
+            np.testing.assert_allclose(y[b, :k], y1[0], rtol=0, atol=0)
+            np.testing.assert_allclose(kn[b, :k], k1[0], rtol=0, atol=0)
+            np.testing.assert_allclose(vn[b, :k], v1[0], rtol=0, atol=0)
+        assert not y[b, k:].any() and not kn[b, k:].any() and not vn[b, k:].any()
+    # image 2 keeps everything: the independent scalar dense block on its own prior rows
+    Wl = {n: a.tolist() for n, a in W.items()}
+    ref, rk, rv = _dense_block_scalar(x[2].tolist(), Wl, kp[2, :4].tolist(), vp[2, :4].tolist(), 2)
+    np.testing.assert_allclose(y[2], np.array(ref), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(kn[2], np.array(rk), rtol=1e-10, atol=1e-12)
+
+
+def test_per_image_counts_nothing_leaks_between_images_or_from_unused_rows():
+    rng = np.random.default_rng(22)
+    x, W, kp, vp, idx, counts, kv_rows = _ragged_case(rng)
+    y, kn, vn = O.pruned_block(x, idx, W, kp, vp, heads=2, kv_rows=kv_rows)
+    # prior rows past an image's own count, and another image's tokens, are never read
+    kp2, vp2, x2 = kp.copy(), vp.copy(), x.copy()
+    for b, P in enumerate(kv_rows):
+        kp2[b, P:] = np.nan
+        vp2[b, P:] = np.nan
+    x2[1] = np.nan                                       # image 1 keeps nothing: its tokens are never gathered
+    y2, kn2, vn2 = O.pruned_block(x2, idx, W, kp2, vp2, heads=2, kv_rows=kv_rows)
+    assert np.array_equal(y, y2) and np.array_equal(kn, kn2) and np.array_equal(vn, vn2)
+    # uniform counts written with the per-image arguments are the plain call
+    full = np.tile(np.arange(5), (3, 1))
+    a = O.pruned_block(x, full, W, kp, vp, heads=2)
+    b_ = O.pruned_block(x, full, W, kp, vp, heads=2, kv_rows=[4, 4, 4])
+    for u, v in zip(a, b_):
+        assert np.array_equal(u, v)
+    with pytest.raises(AssertionError):
+        O.pruned_block(x, np.array([[0, -1, 3]] * 3), W, kp, vp, heads=2)      # a hole is not a tail
+
+
+def test_merge_with_per_image_counts():
+    rng = np.random.default_rng(23)
+    B, hp, wp, h, w, C = 3, 3, 3, 4, 4, 5
+    N = h * w
+    x = rng.standard_normal((B, N, C))
+    cache_prev = rng.standard_normal((B, hp * wp, C))
+    counts = [3, 0, N]
+    idx = np.full((B, N), -1, dtype=np.int64)
+    idx[0, :3] = [2, 7, 11]
+    idx[2] = np.arange(N)
+    y = rng.standard_normal((B, N, C))
+    for b, k in enumerate(counts):
+        y[b, k:] = np.nan                                # rows behind an image's count must never be used
+    out, cn = O.merge_cache(x, y, idx, cache_prev, hp, wp, h, w)
+    assert np.isfinite(out).all() and np.isfinite(cn).all()
+    for b, k in enumerate(counts):
+        o1, c1 = O.merge_cache(x[b:b + 1], y[b:b + 1, :k], idx[b:b + 1, :k], cache_prev[b:b + 1], hp, wp, h, w)
+        assert np.array_equal(out[b], o1[0]) and np.array_equal(cn[b], c1[0])
+    up = O.bilinear_upsample(cache_prev, hp, wp, h, w)
+    np.testing.assert_allclose(out[1], x[1] + up[1], atol=0)           # nothing kept: everything from the cache
+    assert np.array_equal(out[2], y[2])                                 # everything kept
