@@ -239,6 +239,31 @@ int nova_pruned_block_variant(nova_ctx* ctx, void* stream, const nova_block_shap
                               void* y_kept, void* workspace, size_t workspace_bytes);
 
 /*
+ * nova_pruned_block_variant with per-image keep counts on the device (Sec. 3.3, "Dual-Linkage Acceleration": the
+ * scale- and layer-linkage ratios are per instance, so the images of a batch keep different numbers of tokens),
+ * so that nova_layer_ratio -> nova_select -> this call -> nova_merge_cache_rows run without a host round trip.
+ *   shape->k          row pitch: kept_idx is [B, k], y_kept [B, k, C], and no image keeps more (k = N is always safe).
+ *                     Launch sizes and the workspace follow this k; output tiles and query blocks that hold no
+ *                     live row leave at once, so the work done follows the counts.
+ *   k_per_row         DEVICE int32 [B] or NULL (= k for every image): image b keeps the tokens kept_idx[b, 0 ..
+ *                     k_per_row[b]) (clamped to [0, k]); the rest of its row is ignored (nova_select writes -1 there)
+ *   shape->kv_len     upper bound of the images' prior-row counts; shape->kv_len + shape->k <= kv_capacity
+ *   kv_len_per_row    DEVICE int32 [B] or NULL (= kv_len for every image): rows already in image b's K/V cache
+ *                     (clamped to [0, kv_len]).  Image b attends to those rows plus its own kept rows, which are
+ *                     appended right behind them.
+ *   kv_len_next       DEVICE int32 [B] or NULL: receives kv_len_per_row[b] + k_per_row[b], the image's cache length
+ *                     after this block; may be the kv_len_per_row array itself (it is written after every read)
+ *   y_kept            rows [b, s] with s >= k_per_row[b] are undefined (some are never written)
+ * Every image's result is that of a single-image call with its own counts.  Everything else (variant may be NULL)
+ * as nova_pruned_block_variant.  The three count arrays must be 4-byte aligned.
+ */
+int nova_pruned_block_rows(nova_ctx* ctx, void* stream, const nova_block_shape* shape,
+                           const nova_block_weights* weights, const nova_block_variant* variant,
+                           const int32_t* k_per_row, const int32_t* kv_len_per_row, int32_t* kv_len_next,
+                           const void* x, const int32_t* kept_idx, void* k_cache, void* v_cache, void* y_kept,
+                           void* workspace, size_t workspace_bytes);
+
+/*
  * Residual cache reuse (Sec. 3.3, "Residual Cache Reuse", second and third equations):
  *   cache_up   = bilinear upsample of cache_prev from the (hp, wp) grid to (h, w),
  *                half-pixel centres, evaluated in fp32
@@ -273,10 +298,22 @@ int nova_merge_cache_interp(nova_ctx* ctx, void* stream, int dtype, int interp, 
                             const uint8_t* keep_mask, const void* cache_prev, void* out, void* cache_new);
 
 /*
+ * nova_merge_cache_interp with per-image keep counts on the device (see nova_pruned_block_rows):
+ *   k           row pitch of kept_idx [B, k] and y_kept [B, k, C]
+ *   k_per_row   DEVICE int32 [B] or NULL (= k for every image): only slots [0, k_per_row[b]) of image b are scattered
+ *               back (clamped to [0, k]; a slot holding -1 is skipped as well); every other token of the image is
+ *               filled from the cache, as keep_mask says.  With k_per_row given, cache_prev is required whatever k is.
+ */
+int nova_merge_cache_rows(nova_ctx* ctx, void* stream, int dtype, int interp, int B, int C, int h, int w, int hp,
+                          int wp, int k, const int32_t* k_per_row, const void* x, const void* y_kept,
+                          const int32_t* kept_idx, const uint8_t* keep_mask, const void* cache_prev, void* out,
+                          void* cache_new);
+
+/*
  * Ratio controllers (Sec. 3.3, "Adaptive Acceleration Activation" and "Dual-Linkage
  * Acceleration").  The first two are host arithmetic on one instance's scale mean entropies
  * (no GPU work, ctx-free); the third runs on the device so that a layer's keep counts reach
- * nova_select (its k_per_row argument) without a host round trip.
+ * nova_select, nova_pruned_block_rows and nova_merge_cache_rows (their k_per_row argument) without a host round trip.
  *
  * nova_activation_scale: with g_t = Hbar_t - Hbar_{t-1}, eta = mean of g_2..g_{t_est} and
  * g~_t = (g_t + g_{t-1}) / 2, *t_star is the earliest t >= t_est + 1 (1-based) with

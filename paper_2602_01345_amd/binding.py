@@ -121,6 +121,11 @@ def load_library() -> C.CDLL:
     lib.nova_pruned_block_variant.argtypes = [vp, vp, C.POINTER(_Shape), C.POINTER(_Weights), C.POINTER(_Variant),
                                               vp, vp, vp, vp, vp, vp, C.c_size_t]
     lib.nova_pruned_block_variant.restype = i32
+    lib.nova_pruned_block_rows.argtypes = [vp, vp, C.POINTER(_Shape), C.POINTER(_Weights), C.POINTER(_Variant),
+                                           vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t]
+    lib.nova_pruned_block_rows.restype = i32
+    lib.nova_merge_cache_rows.argtypes = [vp, vp, i32, i32] + [i32] * 7 + [vp] * 8
+    lib.nova_merge_cache_rows.restype = i32
     lib.nova_merge_cache.argtypes = [vp, vp, i32] + [i32] * 7 + [vp] * 7
     lib.nova_merge_cache_interp.argtypes = [vp, vp, i32, i32] + [i32] * 7 + [vp] * 7
     lib.nova_merge_cache_interp.restype = i32
@@ -316,6 +321,37 @@ class Nova:
                                                 _ptr(k_cache), _ptr(v_cache), _ptr(y_kept), _ptr(workspace),
                                                 workspace.numel() * workspace.element_size())
         self._check(rc, "nova_pruned_block_variant")
+
+    def pruned_block_rows(self, shape: BlockShape, weights: Dict[str, Optional[torch.Tensor]],
+                          variant: Optional[BlockVariant], k_per_row: Optional[torch.Tensor],
+                          kv_len_per_row: Optional[torch.Tensor], kv_len_next: Optional[torch.Tensor],
+                          x: torch.Tensor, kept_idx: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                          y_kept: torch.Tensor, workspace: torch.Tensor):
+        """nova_pruned_block_rows: per-image keep counts / cache lengths as int32 device tensors [B]."""
+        for t in (k_per_row, kv_len_per_row, kv_len_next):
+            assert t is None or t.dtype == torch.int32
+        s = shape.c_struct()
+        w = _Weights(*[_ptr(weights.get(n)) for n, _ in _Weights._fields_])
+        v = variant.c_struct() if variant is not None else None
+        rc = self.lib.nova_pruned_block_rows(self.ctx, _stream(), C.byref(s), C.byref(w),
+                                             C.byref(v) if v is not None else None, _ptr(k_per_row),
+                                             _ptr(kv_len_per_row), _ptr(kv_len_next), _ptr(x), _ptr(kept_idx),
+                                             _ptr(k_cache), _ptr(v_cache), _ptr(y_kept), _ptr(workspace),
+                                             workspace.numel() * workspace.element_size())
+        self._check(rc, "nova_pruned_block_rows")
+
+    def merge_cache_rows(self, interp: int, h: int, w: int, hp: int, wp: int, k: int,
+                         k_per_row: Optional[torch.Tensor], x: torch.Tensor, y_kept: Optional[torch.Tensor],
+                         kept_idx: Optional[torch.Tensor], keep_mask: torch.Tensor,
+                         cache_prev: Optional[torch.Tensor], out: torch.Tensor,
+                         cache_new: Optional[torch.Tensor] = None):
+        """nova_merge_cache_rows: k is the row pitch, k_per_row the per-image counts (int32 device [B])."""
+        assert k_per_row is None or k_per_row.dtype == torch.int32
+        B, _, Cc = x.shape
+        rc = self.lib.nova_merge_cache_rows(self.ctx, _stream(), _dtype_code(x), interp, B, Cc, h, w, hp, wp, k,
+                                            _ptr(k_per_row), _ptr(x), _ptr(y_kept), _ptr(kept_idx), _ptr(keep_mask),
+                                            _ptr(cache_prev), _ptr(out), _ptr(cache_new))
+        self._check(rc, "nova_merge_cache_rows")
 
     # -- nova_merge_cache -----------------------------------------------------------
     def merge_cache(self, h: int, w: int, hp: int, wp: int, k: int, x: torch.Tensor,

@@ -295,7 +295,19 @@ int nova_pruned_block_variant(nova_ctx* ctx, void* stream, const nova_block_shap
                               const nova_block_weights* weights, const nova_block_variant* variant,
                               const void* x, const int32_t* kept_idx, void* k_cache, void* v_cache, void* y_kept,
                               void* workspace, size_t workspace_bytes) {
+  return nova_pruned_block_rows(ctx, stream, shape, weights, variant, nullptr, nullptr, nullptr, x, kept_idx, k_cache,
+                                v_cache, y_kept, workspace, workspace_bytes);
+}
+
+int nova_pruned_block_rows(nova_ctx* ctx, void* stream, const nova_block_shape* shape,
+                           const nova_block_weights* weights, const nova_block_variant* variant,
+                           const int32_t* k_per_row, const int32_t* kv_len_per_row, int32_t* kv_len_next,
+                           const void* x, const int32_t* kept_idx, void* k_cache, void* v_cache, void* y_kept,
+                           void* workspace, size_t workspace_bytes) {
   if (!ctx || !weights) return NOVA_ERR_INVALID_ARG;
+  for (const void* p : {(const void*)k_per_row, (const void*)kv_len_per_row, (const void*)kv_len_next})
+    if (reinterpret_cast<uintptr_t>(p) & 3) return NOVA_ERR_INVALID_ARG;
+  const RowCounts rows = {k_per_row, kv_len_per_row, kv_len_next};
   nova_block_variant var = {};
   if (variant) var = *variant;
   if ((var.gelu_tanh != 0 && var.gelu_tanh != 1) || (var.qk_norm != 0 && var.qk_norm != 1))
@@ -329,9 +341,9 @@ int nova_pruned_block_variant(nova_ctx* ctx, void* stream, const nova_block_shap
   hipStream_t st = static_cast<hipStream_t>(stream);
   hipError_t e;
   if (shape->dtype == NOVA_BF16)
-    e = launch_block_bf16(ctx, st, *shape, *weights, var, x, kept_idx, k_cache, v_cache, y_kept, ws);
+    e = launch_block_bf16(ctx, st, *shape, *weights, var, rows, x, kept_idx, k_cache, v_cache, y_kept, ws);
   else
-    e = launch_block_f32(ctx, st, *shape, *weights, var, static_cast<const float*>(x), kept_idx,
+    e = launch_block_f32(ctx, st, *shape, *weights, var, rows, static_cast<const float*>(x), kept_idx,
                          static_cast<float*>(k_cache), static_cast<float*>(v_cache), static_cast<float*>(y_kept), ws);
   return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
 }
@@ -346,7 +358,16 @@ int nova_merge_cache(nova_ctx* ctx, void* stream, int dtype, int B, int C, int h
 int nova_merge_cache_interp(nova_ctx* ctx, void* stream, int dtype, int interp, int B, int C, int h, int w, int hp,
                             int wp, int k, const void* x, const void* y_kept, const int32_t* kept_idx,
                             const uint8_t* keep_mask, const void* cache_prev, void* out, void* cache_new) {
+  return nova_merge_cache_rows(ctx, stream, dtype, interp, B, C, h, w, hp, wp, k, nullptr, x, y_kept, kept_idx,
+                               keep_mask, cache_prev, out, cache_new);
+}
+
+int nova_merge_cache_rows(nova_ctx* ctx, void* stream, int dtype, int interp, int B, int C, int h, int w, int hp,
+                          int wp, int k, const int32_t* k_per_row, const void* x, const void* y_kept,
+                          const int32_t* kept_idx, const uint8_t* keep_mask, const void* cache_prev, void* out,
+                          void* cache_new) {
   if (!ctx) return NOVA_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(k_per_row) & 3) return NOVA_ERR_INVALID_ARG;
   if (interp != NOVA_INTERP_BILINEAR && interp != NOVA_INTERP_NEAREST && interp != NOVA_INTERP_BICUBIC)
     return NOVA_ERR_INVALID_ARG;
   if (!valid_dtype(dtype)) return NOVA_ERR_UNSUPPORTED;
@@ -357,7 +378,8 @@ int nova_merge_cache_interp(nova_ctx* ctx, void* stream, int dtype, int interp, 
   if (C % (16 / (int)esize(dtype)) != 0) return NOVA_ERR_UNSUPPORTED;
   if (!x || !out || !keep_mask || out == x) return NOVA_ERR_INVALID_ARG;
   if (k > 0 && (!y_kept || !kept_idx)) return NOVA_ERR_INVALID_ARG;
-  if (k < N && (!cache_prev || hp < 1 || wp < 1)) return NOVA_ERR_INVALID_ARG;
+  // with per-image counts some image may keep fewer than k tokens: the prior cache is needed whatever k is
+  if ((k < N || k_per_row) && (!cache_prev || hp < 1 || wp < 1)) return NOVA_ERR_INVALID_ARG;
   if (hp < 1 || wp < 1) cache_prev = nullptr;   // only reachable with k == N: an empty prior grid is never sampled
   const void* ptrs[] = {x, y_kept, cache_prev, out, cache_new};
   for (const void* p : ptrs)
@@ -365,7 +387,7 @@ int nova_merge_cache_interp(nova_ctx* ctx, void* stream, int dtype, int interp, 
   if (int rc = set_device(ctx)) return rc;
   StageTimer timer(ctx, static_cast<hipStream_t>(stream), NOVA_STAGE_MERGE);
   hipError_t e = launch_merge(static_cast<hipStream_t>(stream), dtype, interp, B, C, h, w, hp, wp, k, x, y_kept, kept_idx,
-                              keep_mask, cache_prev, out, cache_new);
+                              keep_mask, cache_prev, out, cache_new, k_per_row);
   return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;
 }
 

@@ -36,7 +36,8 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 }
 
 constexpr int BKV = 64;              // keys per tile
-constexpr int kMaxSplit = 4;         // sizes the partial-result workspace: kMaxSplit * B * k * C floats
+constexpr int kMaxSplit = 4;         // the partial-result workspace holds kMaxSplit partials per item on average; the
+                                     // items of the last round alone are cut, into up to 16 key runs each
 
 // MFMA row i of a 32-key block reads key pi(i), chosen so that the 8 scores a lane ends up holding
 // in registers 0..7 (and 8..15) belong to 8 consecutive keys: exactly the 8-key run the P^T operand
@@ -56,8 +57,9 @@ __device__ __forceinline__ int swz(int r, int c) {
 template <int DH, int NQ, int NST, int OCC, int NW>
 __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc, int k, int C,
-    int heads, int cap, int kv_total, int nqb, int n_whole, int nsplit,
-    bf16_t* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml) {
+    int heads, int cap, int kv_total_uniform, int nqb, int n_whole, int nsplit,
+    bf16_t* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml,
+    const int32_t* __restrict__ k_rows, const int32_t* __restrict__ kv_rows, int P, int self_keys) {
   constexpr int KROWB = DH * 2;                  // bytes per key row of the K tile
   constexpr int KCH = KROWB / 16;                // chunks per key row
   constexpr int K_BYTES = BKV * KROWB;
@@ -96,6 +98,23 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
   const int b = bh / heads, head = bh - b * heads;
   const bf16_t* Kg = kc + (int64_t)bh * cap * DH;          // [cap][DH]
   const bf16_t* Vg = vc + (int64_t)bh * DH * (int64_t)cap; // [DH][cap]
+  // Per-image keep counts: image b's queries are slots [0, kq) of its k-slot segment and its keys are its own
+  // prior rows plus its own kq kept rows (self-attention; a cross-attention call has the same keys for every image).
+  const int kq = image_count(k_rows, b, k);
+  const int kv_total = self_keys && (k_rows || kv_rows) ? image_prior(kv_rows, b, P) + kq : kv_total_uniform;
+  if (qb * (NW * NQ * 32) >= kq) {
+    // no live query in this block (the whole workgroup leaves, before any barrier): an uncut item zeroes its
+    // rows of the output, the rows of a cut item are zeroed by the merge pass
+    if (whole) {
+      constexpr int CPR = DH / 8;                            // 16-byte chunks per row of this head
+      const int r0 = qb * (NW * NQ * 32), r1 = min(r0 + NW * NQ * 32, k);
+      for (int i = tid; i < (r1 - r0) * CPR; i += NW * 64) {
+        const int r = r0 + i / CPR, c = i % CPR;
+        *reinterpret_cast<u32x4*>(out + ((int64_t)b * k + r) * C + head * DH + c * 8) = u32x4{0u, 0u, 0u, 0u};
+      }
+    }
+    return;
+  }
 
   // ---- query fragments (B operand): lane = query column, 8 dh elements per K step ----------
   bf16x8 qf[NQ][KSTEPS];
@@ -103,7 +122,7 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
 #pragma unroll
   for (int g = 0; g < NQ; ++g) {
     qi[g] = qb * BQ + (wave * NQ + g) * 32 + col;
-    const int qrow = min(qi[g], k - 1);                    // clamped past the edge; never stored
+    const int qrow = min(qi[g], kq - 1);                   // clamped past the last live query; never stored
     const bf16_t* qp = q + ((int64_t)b * k + qrow) * C + head * DH + half * 8;
 #pragma unroll
     for (int t = 0; t < KSTEPS; ++t) qf[g][t] = *reinterpret_cast<const bf16x8*>(qp + t * 16);
@@ -176,7 +195,20 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
   const int ntiles_all = (kv_total + BKV - 1) / BKV;
   const int tps = (ntiles_all + nparts - 1) / nparts;
   const int t_begin = split * tps;
-  const int ntiles = min(ntiles_all, t_begin + tps);       // exclusive end; >= t_begin + 1 (host guarantees)
+  const int ntiles = min(ntiles_all, t_begin + tps);       // exclusive end
+  if (t_begin >= ntiles_all) {
+    // an empty key run (only with per-image counts: this image has fewer key tiles than the launch was planned
+    // for): an all-zero partial with reference -inf, which the merge pass weighs with 0.  Leaves before any barrier.
+#pragma unroll
+    for (int g = 0; g < NQ; ++g) {
+      if (qi[g] >= kq) continue;
+      const int64_t prow = (int64_t)pidx * BQ + (qi[g] - qb * BQ);
+      for (int d = half * (DH / 2); d < (half + 1) * (DH / 2); d += 4)
+        *reinterpret_cast<f32x4*>(part_o + prow * DH + d) = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (half == 0) { part_ml[prow * 2] = -INFINITY; part_ml[prow * 2 + 1] = 0.f; }
+    }
+    return;
+  }
 #pragma unroll
   for (int t = 0; t < NST - 1; ++t)
     if (t_begin + t < ntiles) issue(t, (t_begin + t) * BKV);
@@ -186,7 +218,7 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
 
   // The last query block of an (image, head) is ragged: waves with no kept query leave the matrix core and the
   // vector units to the other workgroup of the CU.
-  const bool wave_live = qb * BQ + wave * NQ * 32 < k;
+  const bool wave_live = qb * BQ + wave * NQ * 32 < kq;
   // A-operand row of this lane inside a 32-key block (see key_of_mfma_row)
   const int krow = key_of_mfma_row(col);
   // One 64-key tile.  TAIL (last tile only) masks the scores of keys past kv_total.  stage_v is the ring stage
@@ -394,6 +426,17 @@ __global__ __launch_bounds__(NW * 64, OCC) void attention_bf16_kernel(
     const float l_tot = l_run[g] + __shfl_xor(l_run[g], 32, NOVA_WAVE);
     if (qi[g] >= k) continue;
     const int64_t row = (int64_t)b * k + qi[g];
+    if (qi[g] >= kq) {
+      // a slot past this image's keep count: zeros (an uncut item; the merge pass does it for cut ones)
+      if (nparts == 1) {
+        bf16_t* op = out + row * C + head * DH;
+#pragma unroll
+        for (int d = 0; d < DB; ++d)
+#pragma unroll
+          for (int r4 = 0; r4 < 4; ++r4) *reinterpret_cast<u32x2*>(op + d * 32 + r4 * 8 + half * 4) = u32x2{0u, 0u};
+      }
+      continue;
+    }
     if (nparts == 1) {
       const float inv = 1.0f / l_tot;
       bf16_t* op = out + row * C + head * DH;
@@ -437,7 +480,7 @@ constexpr int kCombineRows = 8;
 template <int DH, int BQ>
 __global__ __launch_bounds__(kCombineRows * (DH / 4)) void attention_combine_kernel(
     const float* __restrict__ part_o, const float* __restrict__ part_ml, int k, int C, int heads, int nqb,
-    int n_whole, int nsplit, bf16_t* __restrict__ out) {
+    int n_whole, int nsplit, bf16_t* __restrict__ out, const int32_t* __restrict__ k_rows) {
   constexpr int CHUNKS = BQ / kCombineRows;                         // workgroups per item
   const int ci = blockIdx.x / CHUNKS, chunk = blockIdx.x - ci * CHUNKS;
   const int item = n_whole + ci;
@@ -447,6 +490,10 @@ __global__ __launch_bounds__(kCombineRows * (DH / 4)) void attention_combine_ker
   const int c = (threadIdx.x % (DH / 4)) * 4;
   const int qrow = qb * BQ + qr;
   if (qrow >= k) return;
+  if (qrow >= image_count(k_rows, b, k)) {                          // a slot past its image's keep count: zeros
+    *reinterpret_cast<u32x2*>(out + ((int64_t)b * k + qrow) * C + head * DH + c) = u32x2{0u, 0u};
+    return;
+  }
   const int64_t p0 = (int64_t)ci * nsplit;                          // first partial of this item
   float mmax = -INFINITY;
   for (int s = 0; s < nsplit; ++s) mmax = fmaxf(mmax, part_ml[((p0 + s) * BQ + qr) * 2]);
@@ -469,7 +516,7 @@ __global__ __launch_bounds__(kCombineRows * (DH / 4)) void attention_combine_ker
 template <int DH, int NQ, int NST, int OCC, int NW>
 hipError_t launch_cfg(const nova_ctx* ctx, hipStream_t st, const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int B,
                       int k, int C, int heads, int cap, int kv_total, bf16_t* out, float* part_o,
-                      float* part_ml) {
+                      float* part_ml, const int32_t* k_rows, const int32_t* kv_rows, int P, int self_keys) {
   constexpr int BQ = NW * NQ * 32;
   const int nqb = (k + BQ - 1) / BQ;
   const int items = nqb * heads * B;                      // (batch row, head, query block)
@@ -518,10 +565,10 @@ hipError_t launch_cfg(const nova_ctx* ctx, hipStream_t st, const bf16_t* q, cons
   }
   const int grid = n_whole + (items - n_whole) * nsplit;
   attention_bf16_kernel<DH, NQ, NST, OCC, NW><<<grid, NW * 64, 0, st>>>(
-      q, kc, vc, k, C, heads, cap, kv_total, nqb, n_whole, nsplit, out, part_o, part_ml);
+      q, kc, vc, k, C, heads, cap, kv_total, nqb, n_whole, nsplit, out, part_o, part_ml, k_rows, kv_rows, P, self_keys);
   if (nsplit > 1)
     attention_combine_kernel<DH, BQ><<<(items - n_whole) * (BQ / kCombineRows), kCombineRows * (DH / 4), 0, st>>>(
-        part_o, part_ml, k, C, heads, nqb, n_whole, nsplit, out);
+        part_o, part_ml, k, C, heads, nqb, n_whole, nsplit, out, k_rows);
   return hipGetLastError();
 }
 
@@ -531,7 +578,8 @@ int attention_max_split() { return kMaxSplit; }
 
 hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void* qv, const void* kcv,
                                  const void* vcv, int B, int k, int C, int heads, int cap, int kv_total,
-                                 void* outv, float* part_o, float* part_ml) {
+                                 void* outv, float* part_o, float* part_ml, const int32_t* k_rows,
+                                 const int32_t* kv_rows, int P, int self_keys) {
   const bf16_t* q = static_cast<const bf16_t*>(qv);
   const bf16_t* kc = static_cast<const bf16_t*>(kcv);
   const bf16_t* vc = static_cast<const bf16_t*>(vcv);
@@ -546,7 +594,7 @@ hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void
   if (nq < 1 || nq > 4) nq = 1;
 #define ATT_LAUNCH(DH_, NQ_, NST_, OCC_, NW_)                                                                       \
   return launch_cfg<DH_, NQ_, NST_, OCC_, NW_>(ctx, st, q, kc, vc, B, k, C, heads, cap, kv_total, out, \
-                                               part_o, part_ml)
+                                               part_o, part_ml, k_rows, kv_rows, P, self_keys)
   if (dh == 64) {
     if (nq == 1) ATT_LAUNCH(64, 1, 2, 2, 4);
     if (nq == 4) ATT_LAUNCH(64, 1, 2, 3, 4);

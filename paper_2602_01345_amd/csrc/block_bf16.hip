@@ -14,8 +14,9 @@
 #include "nova_internal.h"
 
 hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_shape& s,
-                             const nova_block_weights& w, const nova_block_variant& var, const void* xv,
-                             const int32_t* idx, void* kcv, void* vcv, void* yv, const BlockWorkspace& ws) {
+                             const nova_block_weights& w, const nova_block_variant& var, const RowCounts& rc,
+                             const void* xv, const int32_t* idx, void* kcv, void* vcv, void* yv,
+                             const BlockWorkspace& ws) {
   const int M = s.B * s.k, C = s.C, F = s.C * s.ffn_mult, dh = s.C / s.heads;
   const bf16_t* x = static_cast<const bf16_t*>(xv);
   bf16_t* kc = static_cast<bf16_t*>(kcv);
@@ -35,13 +36,14 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
   hipError_t e;
   {
     StageTimer t(ctx, st, NOVA_STAGE_GATHER_LN);
-    e = launch_gather_ln(st, NOVA_BF16, x, idx, M, s.k, s.N, C, ada_row(0), ada_row(1), ada_pitch, u);
+    e = launch_gather_ln(st, NOVA_BF16, x, idx, M, s.k, s.N, C, ada_row(0), ada_row(1), ada_pitch, u, rc.k_rows);
   }
   if (e != hipSuccess) return e;
 
   EpiParams<bf16_t> ep = {};
   ep.C = C; ep.heads = s.heads; ep.dh = dh; ep.cap = s.kv_capacity; ep.P = s.kv_len; ep.k = s.k;
   ep.idx = idx; ep.Ntok = s.N;
+  ep.k_rows = rc.k_rows; ep.kv_rows = rc.kv_rows;
   ep.gate_pitch = ada_pitch;
   ep.part = reinterpret_cast<float*>(ws.part_o);          // free once attention is done: K-slice sums of the projections back to C
 
@@ -53,14 +55,16 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
     StageTimer t(ctx, st, NOVA_STAGE_QKV);
     e = launch_gemm_bf16(ctx, st, EPI_QKV, u, w.w_qkv, M, 3 * C, C, ep);
     if (e == hipSuccess && var.qk_norm)
-      e = launch_qk_norm(st, NOVA_BF16, q, kc, var.qk_scale, kAttnLog2e, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len);
+      e = launch_qk_norm(st, NOVA_BF16, q, kc, var.qk_scale, kAttnLog2e, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len,
+                         rc.k_rows, rc.kv_rows);
   }
   if (e != hipSuccess) return e;
 
   {
     StageTimer t(ctx, st, NOVA_STAGE_ATTENTION);
     e = launch_attention_bf16(ctx, st, q, kc, vc, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len + s.k, attn,
-                              reinterpret_cast<float*>(ws.part_o), reinterpret_cast<float*>(ws.part_ml));
+                              reinterpret_cast<float*>(ws.part_o), reinterpret_cast<float*>(ws.part_ml), rc.k_rows,
+                              rc.kv_rows, s.kv_len, 1);
   }
   if (e != hipSuccess) return e;
 
@@ -74,7 +78,7 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
     // cross-attention sub-layer over the condition tokens: LN -> query projection -> attention over the
     // text keys / values -> output projection added to x1 in place (each output element is read and
     // written by the same thread)
-    e = launch_gather_ln(st, NOVA_BF16, x1, nullptr, M, s.k, s.N, C, nullptr, nullptr, 0, u);
+    e = launch_gather_ln(st, NOVA_BF16, x1, nullptr, M, s.k, s.N, C, nullptr, nullptr, 0, u, rc.k_rows);
     if (e != hipSuccess) return e;
     ep.bias = static_cast<const bf16_t*>(var.b_cq); ep.out = q; ep.ldo = C; ep.gate = nullptr;
     ep.q_scale = kAttnLog2e / sqrtf((float)dh);
@@ -82,7 +86,7 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
     if (e != hipSuccess) return e;
     e = launch_attention_bf16(ctx, st, q, var.k_text, var.v_text, s.B, s.k, C, s.heads, var.text_capacity,
                               var.text_len, attn, reinterpret_cast<float*>(ws.part_o),
-                              reinterpret_cast<float*>(ws.part_ml));
+                              reinterpret_cast<float*>(ws.part_ml), rc.k_rows, nullptr, 0, 0);
     if (e != hipSuccess) return e;
     ep.bias = static_cast<const bf16_t*>(var.b_co); ep.out = x1; ep.ldo = C; ep.res = x1;
     e = launch_gemm_bf16(ctx, st, EPI_RESIDUAL, attn, var.w_co, M, C, C, ep);
@@ -90,7 +94,8 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
   }
   {
     StageTimer t(ctx, st, NOVA_STAGE_LN2);
-    e = launch_gather_ln(st, NOVA_BF16, x1, nullptr, M, s.k, s.N, C, ada_row(3), ada_row(4), ada_pitch, u);
+    e = launch_gather_ln(st, NOVA_BF16, x1, nullptr, M, s.k, s.N, C, ada_row(3), ada_row(4), ada_pitch, u, rc.k_rows,
+                         rc.kv_rows, rc.kv_next, s.kv_len);
   }
   if (e != hipSuccess) return e;
 

@@ -36,13 +36,24 @@ __global__ __launch_bounds__(kTile* kTile) void gemm_f32_kernel(const float* __r
 __global__ __launch_bounds__(NOVA_WAVE) void attention_f32_kernel(const float* __restrict__ q,
                                                                   const float* __restrict__ kc,
                                                                   const float* __restrict__ vc, int k, int C,
-                                                                  int heads, int dh, int cap, int kv_total,
-                                                                  float scale, float* __restrict__ out) {
+                                                                  int heads, int dh, int cap, int kv_total_uniform,
+                                                                  float scale, float* __restrict__ out,
+                                                                  const int32_t* __restrict__ k_rows,
+                                                                  const int32_t* __restrict__ kv_rows, int P,
+                                                                  int self_keys) {
   extern __shared__ float sc[];            // [kv_total] scores, then [dh] the query
-  float* qs = sc + kv_total;
   const int lane = threadIdx.x;
   const int m = blockIdx.x, head = blockIdx.y;
   const int b = m / k;
+  // per-image keep counts: a slot past its image's count gets zeros; an image's keys are its own prior rows plus
+  // its own kept rows (never more than the uniform total the LDS was sized for)
+  const int kq = image_count(k_rows, b, k);
+  if (m - b * k >= kq) {
+    for (int d = lane; d < dh; d += NOVA_WAVE) out[(int64_t)m * C + head * dh + d] = 0.0f;
+    return;
+  }
+  const int kv_total = self_keys && (k_rows || kv_rows) ? image_prior(kv_rows, b, P) + kq : kv_total_uniform;
+  float* qs = sc + kv_total;
   const int64_t bh = (int64_t)b * heads + head;
   const float* K = kc + bh * cap * dh;
   const float* V = vc + bh * dh * (int64_t)cap;
@@ -82,8 +93,8 @@ void gemm(hipStream_t st, const float* A, const float* W, int M, int Nout, int K
 }  // namespace
 
 hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shape& s, const nova_block_weights& w,
-                            const nova_block_variant& var, const float* x, const int32_t* idx, float* kc, float* vc,
-                            float* y, const BlockWorkspace& ws) {
+                            const nova_block_variant& var, const RowCounts& rc, const float* x, const int32_t* idx,
+                            float* kc, float* vc, float* y, const BlockWorkspace& ws) {
   const int M = s.B * s.k, C = s.C, F = s.C * s.ffn_mult, dh = s.C / s.heads;
   float* u = reinterpret_cast<float*>(ws.u);
   float* q = reinterpret_cast<float*>(ws.q);
@@ -99,12 +110,13 @@ hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shap
   hipError_t e;
   {
     StageTimer t(ctx, st, NOVA_STAGE_GATHER_LN);
-    e = launch_gather_ln(st, NOVA_F32, x, idx, M, s.k, s.N, C, ada_row(0), ada_row(1), ada_pitch, u);
+    e = launch_gather_ln(st, NOVA_F32, x, idx, M, s.k, s.N, C, ada_row(0), ada_row(1), ada_pitch, u, rc.k_rows);
   }
   if (e != hipSuccess) return e;
 
   EpiParams<float> ep = {};
   ep.C = C; ep.heads = s.heads; ep.dh = dh; ep.cap = s.kv_capacity; ep.P = s.kv_len; ep.k = s.k;
+  ep.k_rows = rc.k_rows; ep.kv_rows = rc.kv_rows;
   ep.idx = idx; ep.Ntok = s.N;
   ep.gate_pitch = ada_pitch;
 
@@ -113,7 +125,8 @@ hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shap
     StageTimer t(ctx, st, NOVA_STAGE_QKV);
     gemm<EPI_QKV>(st, u, static_cast<const float*>(w.w_qkv), M, 3 * C, C, ep);
     if (var.qk_norm) {
-      e = launch_qk_norm(st, NOVA_F32, q, kc, var.qk_scale, 1.0f, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len);
+      e = launch_qk_norm(st, NOVA_F32, q, kc, var.qk_scale, 1.0f, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len,
+                         rc.k_rows, rc.kv_rows);
       if (e != hipSuccess) return e;
     }
   }
@@ -123,7 +136,8 @@ hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shap
   {
     StageTimer t(ctx, st, NOVA_STAGE_ATTENTION);
     attention_f32_kernel<<<dim3(M, s.heads), NOVA_WAVE, lds, st>>>(q, kc, vc, s.k, C, s.heads, dh, s.kv_capacity,
-                                                                   kv_total, var.qk_norm ? 1.0f : 1.0f / sqrtf((float)dh), attn);
+                                                                   kv_total, var.qk_norm ? 1.0f : 1.0f / sqrtf((float)dh), attn,
+                                                                   rc.k_rows, rc.kv_rows, s.kv_len, 1);
   }
 
   ep.bias = static_cast<const float*>(w.b_o); ep.out = x1; ep.ldo = C; ep.res = x; ep.gate = ada_row(2);
@@ -133,20 +147,21 @@ hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shap
   }
   if (var.w_cq) {
     // cross-attention sub-layer over the condition tokens (see block_bf16.hip)
-    e = launch_gather_ln(st, NOVA_F32, x1, nullptr, M, s.k, s.N, C, nullptr, nullptr, 0, u);
+    e = launch_gather_ln(st, NOVA_F32, x1, nullptr, M, s.k, s.N, C, nullptr, nullptr, 0, u, rc.k_rows);
     if (e != hipSuccess) return e;
     ep.bias = static_cast<const float*>(var.b_cq); ep.out = q; ep.ldo = C; ep.gate = nullptr;
     gemm<EPI_PLAIN>(st, u, static_cast<const float*>(var.w_cq), M, C, C, ep);
     const size_t lds_t = (size_t)(var.text_len + dh) * sizeof(float);
     attention_f32_kernel<<<dim3(M, s.heads), NOVA_WAVE, lds_t, st>>>(
         q, static_cast<const float*>(var.k_text), static_cast<const float*>(var.v_text), s.k, C, s.heads, dh,
-        var.text_capacity, var.text_len, 1.0f / sqrtf((float)dh), attn);
+        var.text_capacity, var.text_len, 1.0f / sqrtf((float)dh), attn, rc.k_rows, nullptr, 0, 0);
     ep.bias = static_cast<const float*>(var.b_co); ep.out = x1; ep.ldo = C; ep.res = x1;
     gemm<EPI_RESIDUAL>(st, attn, static_cast<const float*>(var.w_co), M, C, C, ep);
   }
   {
     StageTimer t(ctx, st, NOVA_STAGE_LN2);
-    e = launch_gather_ln(st, NOVA_F32, x1, nullptr, M, s.k, s.N, C, ada_row(3), ada_row(4), ada_pitch, u);
+    e = launch_gather_ln(st, NOVA_F32, x1, nullptr, M, s.k, s.N, C, ada_row(3), ada_row(4), ada_pitch, u, rc.k_rows,
+                         rc.kv_rows, rc.kv_next, s.kv_len);
   }
   if (e != hipSuccess) return e;
 

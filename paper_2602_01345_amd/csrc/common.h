@@ -38,6 +38,21 @@ template <> struct Vec16<bf16_t> {
   __device__ __forceinline__ void set(int i, float x) { v[i] = (bf16_t)x; }
 };
 
+// Per-image keep counts (the reduction ratios of Sec. 3.3, "Dual-Linkage Acceleration", are per instance): the
+// kept rows of image b are slots [0, k_b) of its kpitch-row segment, and it holds its own number of prior K/V rows.
+// Null pointers mean "uniform": every image keeps kpitch rows / holds P prior rows.  Values are clamped, so a
+// count the host never saw cannot send a kernel out of bounds.
+__device__ __forceinline__ int image_count(const int32_t* __restrict__ k_rows, int b, int kpitch) {
+  if (!k_rows) return kpitch;
+  const int v = k_rows[b];
+  return v < 0 ? 0 : (v > kpitch ? kpitch : v);
+}
+__device__ __forceinline__ int image_prior(const int32_t* __restrict__ kv_rows, int b, int P) {
+  if (!kv_rows) return P;
+  const int v = kv_rows[b];
+  return v < 0 ? 0 : (v > P ? P : v);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, NOVA_WAVE);

@@ -24,6 +24,11 @@ struct EpiParams {
   T* kc;                // [B, heads, cap, dh]
   T* vc;                // [B, heads, dh, cap]
   int C, heads, dh, cap, P, k;
+  // per-image counts (device, or nullptr = uniform): image b keeps rows [0, k_rows[b]) of its k-row segment and
+  // appends them behind its own kv_rows[b] prior rows; rows past an image's count are computed but never appended,
+  // and output tiles that hold no live row are skipped
+  const int32_t* k_rows;
+  const int32_t* kv_rows;
   // residual sources
   const T* res;         // EPI_ATTN_OUT: x [B, Ntok, C] gathered through idx; EPI_RESIDUAL: x1 [M, C]
   const int32_t* idx;   // [B, k]
@@ -95,10 +100,12 @@ __device__ __forceinline__ void epilogue_store(const EpiParams<T>& p, int row, i
       p.out[(int64_t)row * p.ldo + c] = (T)v;
     } else {
       const int b = row / p.k, s = row - b * p.k;
+      if (s >= image_count(p.k_rows, b, p.k)) return;         // a slot past this image's keep count: nothing to append
+      const int Pb = image_prior(p.kv_rows, b, p.P);
       const int head = c / p.dh, d = c - head * p.dh;
       const int64_t bh = (int64_t)b * p.heads + head;
-      if (sel == 1) p.kc[(bh * p.cap + p.P + s) * p.dh + d] = (T)v;
-      else          p.vc[(bh * p.dh + d) * p.cap + p.P + s] = (T)v;
+      if (sel == 1) p.kc[(bh * p.cap + Pb + s) * p.dh + d] = (T)v;
+      else          p.vc[(bh * p.dh + d) * p.cap + Pb + s] = (T)v;
     }
   } else if (MODE == EPI_ATTN_OUT) {
     const int b = row / p.k;

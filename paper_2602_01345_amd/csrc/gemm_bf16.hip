@@ -117,6 +117,17 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
     }
   };
   set_tile(L);
+  if (ep.k_rows) {
+    // Per-image keep counts: the rows are B segments of ep.k slots and image b fills only the first k_rows[b] of
+    // its segment.  A tile none of whose rows is a live slot has nothing to compute (launches with per-image counts
+    // give every tile its own workgroup, so leaving here skips exactly this tile).  The whole workgroup leaves
+    // together, before the first barrier.
+    const int m_hi = min(m0 + BM, M);
+    bool live = false;
+    for (int b = m0 / ep.k; b * ep.k < m_hi; ++b)
+      live = live || max(m0 - b * ep.k, 0) < image_count(ep.k_rows, b, ep.k);
+    if (!live) return;
+  }
   // load instructions lo..hi-1 (A first, then W) of the tile at K offset k0 into `stage`
   auto issue = [&](int stage, int k0, int lo, int hi) {
     char* sa = lds + stage * STAGE;
@@ -466,7 +477,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
           *reinterpret_cast<bf16x8*>(ep.out + (int64_t)row * ep.ldo + cf) = v;
         } else {
           const int bb = row / ep.k, s = row - bb * ep.k;
-          *reinterpret_cast<bf16x8*>(ep.kc + (((int64_t)bb * ep.heads + head) * ep.cap + ep.P + s) * ep.dh + d) = v;
+          if (s < image_count(ep.k_rows, bb, ep.k))      // slots past an image's keep count append nothing
+            *reinterpret_cast<bf16x8*>(ep.kc + (((int64_t)bb * ep.heads + head) * ep.cap +
+                                                image_prior(ep.kv_rows, bb, ep.P) + s) * ep.dh + d) = v;
         }
       }
     }
@@ -481,9 +494,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
       static_assert(NT % BM == 0, "one thread per tile row and column group");
       const int lrw = tid % BM, cg = tid / BM;
       const int row = m0 + lrw;
-      if (row < M) {
-        const int bb = row / ep.k, s = row - bb * ep.k;
-        bf16_t* vrow = ep.vc + (int64_t)bb * ep.heads * ep.dh * ep.cap + ep.P + s;
+      const int bb = row < M ? row / ep.k : 0, s = row - bb * ep.k;
+      if (row < M && s < image_count(ep.k_rows, bb, ep.k)) {
+        bf16_t* vrow = ep.vc + (int64_t)bb * ep.heads * ep.dh * ep.cap + image_prior(ep.kv_rows, bb, ep.P) + s;
         const int cf0 = n0 - 2 * ep.C;               // value feature of tile column 0
         for (int lc = v_lo + cg; lc < v_hi; lc += CG)
           vrow[(int64_t)(cf0 + lc) * ep.cap] = ct[lrw * CT_PITCH + lc];   // (head * dh + d) * cap
@@ -500,7 +513,8 @@ hipError_t launch_cfg(hipStream_t st, const bf16_t* A, const bf16_t* W, int m_ba
   // that a workgroup's tiles share its XCD)
   constexpr bool PERSIST = persistent_tiles(BM / WM / 32 * (BN / WN / 32), STAGGER, MODE);
   int grid = tiles_m * tiles_n * kslices;
-  if (PERSIST && slots > 0 && slots % 8 == 0 && grid > slots) grid = slots;
+  // (not with per-image keep counts: a workgroup that finds its tile without a live row leaves at once)
+  if (PERSIST && slots > 0 && slots % 8 == 0 && grid > slots && !ep.k_rows) grid = slots;
   gemm_bf16_kernel<BM, BN, WM, WN, BK, NST, STAGGER, MODE><<<grid, WM * WN * 64, 0, st>>>(
       A, W, M, Nout, K, m_base, tiles_m, tiles_n, kslices, ep);
   return hipGetLastError();

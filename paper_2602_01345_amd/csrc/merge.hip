@@ -3,8 +3,11 @@
 // scale's residual cache interpolated to the current grid; the new residual cache is
 // output minus input everywhere.
 //
-// Bandwidth-bound streaming kernel.  One wave64 owns one token row of C channels and
-// moves it in 16-byte vectors; all loads of a sweep are issued before the first use.
+// Bandwidth-bound streaming kernel.  One wave64 owns one row of C channels and moves it in 16-byte vectors; all
+// loads of a sweep are issued before the first use.  The launch has one wave per token (it serves the pruned
+// tokens: a wave whose mask byte says "kept" leaves at once) followed by one wave per kept slot (b, s), which
+// copies row s of the block's output to token kept_idx[b, s] -- so nobody has to look up where in the kept
+// list a token sits.  Per-image keep counts: slots past an image's count (or holding -1) leave at once.
 // The bilinear taps (half-pixel centres) are wave-uniform and evaluated in fp32.  Other interpolation
 // kernels (nearest cell, cubic convolution) go through a generic separable-taps kernel further down.
 #include "common.h"
@@ -14,50 +17,6 @@ namespace {
 
 constexpr int kWavesPerBlock = 4;
 constexpr int kUnroll = 4;
-
-// Position of kept token i in the ascending kept list of its image = the number of kept tokens in front of it.
-// When the image's mask row is 16-byte aligned and a whole number of 16-byte chunks, the wave counts the
-// non-zero mask bytes before i, 16 per lane and step: independent loads, one round trip to memory.  Otherwise a
-// binary search over the index list (log2 k dependent loads).  Both give the same number for a consistent
-// (index list, mask) pair.  Wave-uniform result.
-__device__ __forceinline__ int kept_rank(const uint8_t* __restrict__ mrow, const int32_t* __restrict__ list, int N,
-                                         int k, int i, int lane) {
-  if ((reinterpret_cast<uintptr_t>(mrow) & 15) == 0 && N % 16 == 0) {
-    int cnt = 0;
-    constexpr int kChunks = 4;                             // chunks per lane requested together
-    for (int base = 0; base < i; base += kChunks * NOVA_WAVE * 16) {
-      u32x4 v[kChunks];
-#pragma unroll
-      for (int u = 0; u < kChunks; ++u) {
-        const int j0 = base + (u * NOVA_WAVE + lane) * 16;
-        v[u] = u32x4{0u, 0u, 0u, 0u};
-        if (j0 < i) v[u] = *reinterpret_cast<const u32x4*>(mrow + j0);
-      }
-#pragma unroll
-      for (int u = 0; u < kChunks; ++u) {
-        const int j0 = base + (u * NOVA_WAVE + lane) * 16;
-        const int valid = min(16, i - j0);                 // bytes of this chunk that lie in front of i (<= 0: none)
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-          const int nv = min(max(valid - 4 * d, 0), 4);
-          const uint32_t keep = nv >= 4 ? 0xffffffffu : ((1u << (8 * nv)) - 1u);
-          const uint32_t wd = v[u][d] & keep;
-          const uint32_t nz = (((wd & 0x7f7f7f7fu) + 0x7f7f7f7fu) | wd) & 0x80808080u;   // top bit of every non-zero byte
-          cnt += __popc(nz);
-        }
-      }
-    }
-#pragma unroll
-    for (int o = NOVA_WAVE / 2; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, NOVA_WAVE);
-    return min(cnt, k - 1);
-  }
-  int lo = 0, hi = k - 1;
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    if (list[mid] < i) lo = mid + 1; else hi = mid;
-  }
-  return lo;
-}
 
 struct Taps {
   int i0, i1;
@@ -76,49 +35,80 @@ __device__ __forceinline__ Taps axis_taps(int dst, int n_in, int n_out) {
   return t;
 }
 
+// The wave's job: a pruned token (tok >= 0, slot < 0), a kept slot (both >= 0), or nothing (tok < 0).
+struct MergeItem {
+  int b, tok;
+  int64_t slot;      // row of y_kept, or -1
+};
+__device__ __forceinline__ MergeItem merge_item(int B, int N, int k, const int32_t* __restrict__ idx,
+                                                const uint8_t* __restrict__ mask, const int32_t* __restrict__ k_rows) {
+  const int wave = threadIdx.x / NOVA_WAVE;
+  const int64_t item = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+  const int64_t n_tok = (int64_t)B * N;
+  MergeItem it = {0, -1, -1};
+  if (item < n_tok) {
+    it.b = (int)(item / N);
+    // kept tokens are written by their slot's wave (with k == 0 there are no slots: every token takes this path)
+    if (!mask[item] || k == 0) it.tok = (int)(item - (int64_t)it.b * N);
+  } else if (item - n_tok < (int64_t)B * k) {
+    const int64_t slot = item - n_tok;
+    it.b = (int)(slot / k);
+    const int s = (int)(slot - (int64_t)it.b * k);
+    const int t = s < image_count(k_rows, it.b, k) ? idx[slot] : -1;
+    if (t >= 0 && t < N) { it.tok = t; it.slot = slot; }
+  }
+  return it;
+}
+
+// kept token: the block's output, copied; residual = output - input
+template <typename T>
+__device__ __forceinline__ void merge_kept_row(const T* __restrict__ yr, const T* __restrict__ xr, T* __restrict__ outr,
+                                               T* __restrict__ cnr, int nvec, int lane) {
+  using VT = Vec16<T>;
+  constexpr int VN = VT::N;
+  for (int v0 = 0; v0 < nvec; v0 += kUnroll * NOVA_WAVE) {
+    VT vy[kUnroll], vx[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      int vi = v0 + u * NOVA_WAVE + lane;
+      if (vi < nvec) { vy[u].load(yr + vi * VN); vx[u].load(xr + vi * VN); }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      int vi = v0 + u * NOVA_WAVE + lane;
+      if (vi < nvec) {
+        vy[u].store(outr + vi * VN);
+        if (cnr) {
+          VT c;
+#pragma unroll
+          for (int e = 0; e < VN; ++e) c.set(e, vy[u].get(e) - vx[u].get(e));
+          c.store(cnr + vi * VN);
+        }
+      }
+    }
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void merge_kernel(
     int B, int C, int h, int w, int hp, int wp, int k, const T* __restrict__ x, const T* __restrict__ y,
     const int32_t* __restrict__ idx, const uint8_t* __restrict__ mask, const T* __restrict__ cache_prev,
-    T* __restrict__ out, T* __restrict__ cache_new) {
+    T* __restrict__ out, T* __restrict__ cache_new, const int32_t* __restrict__ k_rows) {
   using VT = Vec16<T>;
   constexpr int VN = VT::N;
   const int lane = threadIdx.x & (NOVA_WAVE - 1);
-  const int wave = threadIdx.x / NOVA_WAVE;
   const int N = h * w;
-  const int64_t row = (int64_t)blockIdx.x * kWavesPerBlock + wave;   // b * N + i
-  if (row >= (int64_t)B * N) return;
-  const int b = (int)(row / N);
-  const int i = (int)(row - (int64_t)b * N);
+  const MergeItem it = merge_item(B, N, k, idx, mask, k_rows);
+  if (it.tok < 0) return;
+  const int b = it.b, i = it.tok;
+  const int64_t row = (int64_t)b * N + i;
   const int nvec = C / VN;                                           // C % VN == 0 (checked by the host)
   const T* xr = x + row * C;
   T* outr = out + row * C;
   T* cnr = cache_new ? cache_new + row * C : nullptr;
 
-  if (mask[row] && k > 0) {
-    const int lo = kept_rank(mask + (int64_t)b * N, idx + (int64_t)b * k, N, k, i, lane);
-    const T* yr = y + ((int64_t)b * k + lo) * C;
-    for (int v0 = 0; v0 < nvec; v0 += kUnroll * NOVA_WAVE) {
-      VT vy[kUnroll], vx[kUnroll];
-#pragma unroll
-      for (int u = 0; u < kUnroll; ++u) {
-        int vi = v0 + u * NOVA_WAVE + lane;
-        if (vi < nvec) { vy[u].load(yr + vi * VN); vx[u].load(xr + vi * VN); }
-      }
-#pragma unroll
-      for (int u = 0; u < kUnroll; ++u) {
-        int vi = v0 + u * NOVA_WAVE + lane;
-        if (vi < nvec) {
-          vy[u].store(outr + vi * VN);
-          if (cnr) {
-            VT c;
-#pragma unroll
-            for (int e = 0; e < VN; ++e) c.set(e, vy[u].get(e) - vx[u].get(e));
-            c.store(cnr + vi * VN);
-          }
-        }
-      }
-    }
+  if (it.slot >= 0) {
+    merge_kept_row<T>(y + it.slot * C, xr, outr, cnr, nvec, lane);
     return;
   }
 
@@ -215,34 +205,22 @@ template <typename T, int NT>
 __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void merge_taps_kernel(
     int B, int C, int h, int w, int hp, int wp, int k, const T* __restrict__ x, const T* __restrict__ y,
     const int32_t* __restrict__ idx, const uint8_t* __restrict__ mask, const T* __restrict__ cache_prev,
-    T* __restrict__ out, T* __restrict__ cache_new) {
+    T* __restrict__ out, T* __restrict__ cache_new, const int32_t* __restrict__ k_rows) {
   using VT = Vec16<T>;
   constexpr int VN = VT::N;
   const int lane = threadIdx.x & (NOVA_WAVE - 1);
-  const int wave = threadIdx.x / NOVA_WAVE;
   const int N = h * w;
-  const int64_t row = (int64_t)blockIdx.x * kWavesPerBlock + wave;   // b * N + i
-  if (row >= (int64_t)B * N) return;
-  const int b = (int)(row / N);
-  const int i = (int)(row - (int64_t)b * N);
+  const MergeItem it = merge_item(B, N, k, idx, mask, k_rows);
+  if (it.tok < 0) return;
+  const int b = it.b, i = it.tok;
+  const int64_t row = (int64_t)b * N + i;
   const int nvec = C / VN;
   const T* xr = x + row * C;
   T* outr = out + row * C;
   T* cnr = cache_new ? cache_new + row * C : nullptr;
 
-  if (mask[row] && k > 0) {       // kept token: the block's output, copied; residual = output - input
-    const int lo = kept_rank(mask + (int64_t)b * N, idx + (int64_t)b * k, N, k, i, lane);
-    const T* yr = y + ((int64_t)b * k + lo) * C;
-    for (int vi = lane; vi < nvec; vi += NOVA_WAVE) {
-      VT vy, vx, c;
-      vy.load(yr + vi * VN); vx.load(xr + vi * VN);
-      vy.store(outr + vi * VN);
-      if (cnr) {
-#pragma unroll
-        for (int e = 0; e < VN; ++e) c.set(e, vy.get(e) - vx.get(e));
-        c.store(cnr + vi * VN);
-      }
-    }
+  if (it.slot >= 0) {
+    merge_kept_row<T>(y + it.slot * C, xr, outr, cnr, nvec, lane);
     return;
   }
   if (!cache_prev) {              // legal only when every token is kept: pass through, zero residual
@@ -293,8 +271,8 @@ __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void merge_taps_kernel(
 template <typename T>
 hipError_t launch_t(hipStream_t st, int interp, int B, int C, int h, int w, int hp, int wp, int k, const void* x,
                     const void* y, const int32_t* idx, const uint8_t* mask, const void* cache_prev, void* out,
-                    void* cache_new) {
-  const int64_t rows = (int64_t)B * h * w;
+                    void* cache_new, const int32_t* k_rows) {
+  const int64_t rows = (int64_t)B * h * w + (int64_t)B * k;          // one wave per token, then one per kept slot
   const unsigned grid = (unsigned)((rows + kWavesPerBlock - 1) / kWavesPerBlock);
   const T* xt = static_cast<const T*>(x);
   const T* yt = static_cast<const T*>(y);
@@ -303,12 +281,13 @@ hipError_t launch_t(hipStream_t st, int interp, int B, int C, int h, int w, int 
   T* nt = static_cast<T*>(cache_new);
   if (interp == NOVA_INTERP_NEAREST)
     merge_taps_kernel<T, 1><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(B, C, h, w, hp, wp, k, xt, yt, idx, mask, ct,
-                                                                       ot, nt);
+                                                                       ot, nt, k_rows);
   else if (interp == NOVA_INTERP_BICUBIC)
     merge_taps_kernel<T, 4><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(B, C, h, w, hp, wp, k, xt, yt, idx, mask, ct,
-                                                                       ot, nt);
+                                                                       ot, nt, k_rows);
   else
-    merge_kernel<T><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(B, C, h, w, hp, wp, k, xt, yt, idx, mask, ct, ot, nt);
+    merge_kernel<T><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(B, C, h, w, hp, wp, k, xt, yt, idx, mask, ct, ot, nt,
+                                                                 k_rows);
   return hipGetLastError();
 }
 
@@ -316,8 +295,8 @@ hipError_t launch_t(hipStream_t st, int interp, int B, int C, int h, int w, int 
 
 hipError_t launch_merge(hipStream_t st, int dtype, int interp, int B, int C, int h, int w, int hp, int wp, int k,
                         const void* x, const void* y, const int32_t* idx, const uint8_t* mask,
-                        const void* cache_prev, void* out, void* cache_new) {
+                        const void* cache_prev, void* out, void* cache_new, const int32_t* k_rows) {
   if (dtype == NOVA_BF16)
-    return launch_t<bf16_t>(st, interp, B, C, h, w, hp, wp, k, x, y, idx, mask, cache_prev, out, cache_new);
-  return launch_t<float>(st, interp, B, C, h, w, hp, wp, k, x, y, idx, mask, cache_prev, out, cache_new);
+    return launch_t<bf16_t>(st, interp, B, C, h, w, hp, wp, k, x, y, idx, mask, cache_prev, out, cache_new, k_rows);
+  return launch_t<float>(st, interp, B, C, h, w, hp, wp, k, x, y, idx, mask, cache_prev, out, cache_new, k_rows);
 }

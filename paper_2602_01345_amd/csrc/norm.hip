@@ -14,12 +14,28 @@ constexpr int kRegVecs = 8;        // 16-byte vectors per lane a row may take to
 template <typename T>
 __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void gather_ln_kernel(
     const T* __restrict__ src, const int32_t* __restrict__ idx, int M, int k, int N, int C,
-    const T* __restrict__ shift, const T* __restrict__ scale, int mod_pitch, T* __restrict__ dst) {
+    const T* __restrict__ shift, const T* __restrict__ scale, int mod_pitch, T* __restrict__ dst,
+    const int32_t* __restrict__ k_rows, const int32_t* __restrict__ kv_rows, int32_t* __restrict__ kv_next, int P) {
   using VT = Vec16<T>;
   constexpr int VN = VT::N;
   const int lane = threadIdx.x & (NOVA_WAVE - 1);
   const int m = blockIdx.x * kWavesPerBlock + threadIdx.x / NOVA_WAVE;
+  if (kv_next && blockIdx.x == 0) {
+    // per-image cache lengths after this block: prior rows + kept rows.  Written by this launch (the second
+    // LayerNorm: everything that reads the old lengths has run), so the output may be the input array.
+    const int B = M / k;
+    for (int b = threadIdx.x; b < B; b += kWavesPerBlock * NOVA_WAVE)
+      kv_next[b] = image_prior(kv_rows, b, P) + image_count(k_rows, b, k);
+  }
   if (m >= M) return;
+  if (k_rows && m % k >= image_count(k_rows, m / k, k)) {
+    // a slot past its image's keep count: zeros, so that everything downstream of it stays finite
+    VT z;
+#pragma unroll
+    for (int e = 0; e < VN; ++e) z.set(e, 0.0f);
+    for (int vi = lane; vi < C / VN; vi += NOVA_WAVE) z.store(dst + (int64_t)m * C + vi * VN);
+    return;
+  }
   int64_t srow = m;
   if (idx) {
     const int b = m / k;
@@ -112,15 +128,16 @@ __global__ __launch_bounds__(kWavesPerBlock* NOVA_WAVE) void gather_ln_kernel(
 }  // namespace
 
 hipError_t launch_gather_ln(hipStream_t st, int dtype, const void* src, const int32_t* idx, int M, int k,
-                            int N, int C, const void* shift, const void* scale, int mod_pitch, void* dst) {
+                            int N, int C, const void* shift, const void* scale, int mod_pitch, void* dst,
+                            const int32_t* k_rows, const int32_t* kv_rows, int32_t* kv_next, int P) {
   const unsigned grid = (unsigned)((M + kWavesPerBlock - 1) / kWavesPerBlock);
   if (dtype == NOVA_BF16)
     gather_ln_kernel<bf16_t><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(
         static_cast<const bf16_t*>(src), idx, M, k, N, C, static_cast<const bf16_t*>(shift),
-        static_cast<const bf16_t*>(scale), mod_pitch, static_cast<bf16_t*>(dst));
+        static_cast<const bf16_t*>(scale), mod_pitch, static_cast<bf16_t*>(dst), k_rows, kv_rows, kv_next, P);
   else
     gather_ln_kernel<float><<<grid, kWavesPerBlock * NOVA_WAVE, 0, st>>>(
         static_cast<const float*>(src), idx, M, k, N, C, static_cast<const float*>(shift),
-        static_cast<const float*>(scale), mod_pitch, static_cast<float*>(dst));
+        static_cast<const float*>(scale), mod_pitch, static_cast<float*>(dst), k_rows, kv_rows, kv_next, P);
   return hipGetLastError();
 }

@@ -68,7 +68,7 @@ hipError_t launch_select(hipStream_t st, const float* H, int B, int N, int k, co
 // merge.hip
 hipError_t launch_merge(hipStream_t st, int dtype, int interp, int B, int C, int h, int w, int hp, int wp, int k,
                         const void* x, const void* y, const int32_t* idx, const uint8_t* mask,
-                        const void* cache_prev, void* out, void* cache_new);
+                        const void* cache_prev, void* out, void* cache_new, const int32_t* k_rows = nullptr);
 
 // Workspace carving for the block (element counts; every region 256-byte aligned).
 struct BlockWorkspace {
@@ -85,17 +85,30 @@ BlockWorkspace carve_workspace(const nova_block_shape& s, void* base);
 
 // norm.hip: dst[m] = LayerNorm(src[row(m)]); with idx, row(m) = (m / k) * N + idx[m], else row(m) = m
 // shift / scale: per-image modulation vectors (image = m / k, row pitch mod_pitch elements), both or neither
+// k_rows: per-image keep counts (device) or nullptr; slots past an image's count get zero rows.  kv_next (with
+// kv_rows, P): the launch also writes the per-image cache lengths after this block, prior rows + kept rows.
 hipError_t launch_gather_ln(hipStream_t st, int dtype, const void* src, const int32_t* idx, int M, int k,
-                            int N, int C, const void* shift, const void* scale, int mod_pitch, void* dst);
+                            int N, int C, const void* shift, const void* scale, int mod_pitch, void* dst,
+                            const int32_t* k_rows = nullptr, const int32_t* kv_rows = nullptr,
+                            int32_t* kv_next = nullptr, int P = 0);
 // qk_norm.hip: queries [B*k, C] and the cache's key rows [P, P+k) scaled to unit length per head, in place;
 // the queries are also multiplied by qk_scale[head]
 hipError_t launch_qk_norm(hipStream_t st, int dtype, void* q, void* kc, const float* qk_scale, float q_mult, int B, int k, int C,
-                          int heads, int cap, int P);
+                          int heads, int cap, int P, const int32_t* k_rows = nullptr, const int32_t* kv_rows = nullptr);
+
+// Per-image counts of one block call (device arrays of B entries, or nullptr = uniform): kept tokens per image
+// (clamped to [0, shape.k], shape.k being the row pitch), prior K/V rows per image (clamped to [0, shape.kv_len]),
+// and where to write the per-image cache lengths after the block (may be the kv_rows array itself).
+struct RowCounts {
+  const int32_t* k_rows;
+  const int32_t* kv_rows;
+  int32_t* kv_next;
+};
 
 // block_f32.hip: plain fp32 kernels (correctness path for small fp32 models)
 hipError_t launch_block_f32(nova_ctx* ctx, hipStream_t st, const nova_block_shape& s, const nova_block_weights& w,
-                            const nova_block_variant& var, const float* x, const int32_t* idx, float* kc, float* vc,
-                            float* y, const BlockWorkspace& ws);
+                            const nova_block_variant& var, const RowCounts& rc, const float* x, const int32_t* idx,
+                            float* kc, float* vc, float* y, const BlockWorkspace& ws);
 // gemm_bf16.hip: out = epilogue(A W^T) on the matrix cores; mode is an EpiMode
 template <typename T> struct EpiParams;
 hipError_t launch_gemm_bf16(const nova_ctx* ctx, hipStream_t st, int mode, const void* A, const void* W, int M,
@@ -118,10 +131,15 @@ size_t head_entropy_partial_bytes(const nova_ctx* ctx, int M, int V, int C);
 // ... * heads * 2 floats), or nullptr to forbid splitting
 int attention_max_split();
 constexpr float kAttnLog2e = 1.4426950408889634f;
+// k_rows / kv_rows (device, or nullptr): per-image keep counts and prior-row counts.  Image b's live queries are
+// slots [0, k_rows[b]) of its k-slot segment (the other slots get zeros); with self_keys its keys are its own
+// kv_rows[b] (default P) prior rows plus its own kept rows, otherwise kv_total keys for every image.
 hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void* q, const void* kc, const void* vc,
                                  int B, int k, int C, int heads, int cap, int kv_total, void* out,
-                                 float* part_o, float* part_ml);
+                                 float* part_o, float* part_ml, const int32_t* k_rows = nullptr,
+                                 const int32_t* kv_rows = nullptr, int P = 0, int self_keys = 1);
 // block_bf16.hip: MFMA path
 hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_shape& s,
-                             const nova_block_weights& w, const nova_block_variant& var, const void* x,
-                             const int32_t* idx, void* kc, void* vc, void* y, const BlockWorkspace& ws);
+                             const nova_block_weights& w, const nova_block_variant& var, const RowCounts& rc,
+                             const void* x, const int32_t* idx, void* kc, void* vc, void* y,
+                             const BlockWorkspace& ws);

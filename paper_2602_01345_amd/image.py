@@ -12,10 +12,12 @@ scales) can be planned: :meth:`ImageRunner.plan_image` lays out static buffers f
 :meth:`ScalePlan.capture` records the scale's launches into a HIP graph, so the many small launches of
 the early scales are replayed with one call instead of being issued one by one from Python.
 
-Keep counts at a pruned scale come either from a table (host integers, no synchronisation) or
-from the layer-linkage controller (``nova_layer_ratio`` on the device).  The block and merge
-calls need one host-side k per launch, so the controller mode reads the rows' counts back once
-per block and keeps the largest for every row of the batch.
+Keep counts at a pruned scale come either from a table (host integers) or from the layer-linkage
+controller (``nova_layer_ratio`` on the device).  In controller mode every image has its own count
+per block and the counts never leave the device: selection, block and merge take them as a device
+array (``nova_select`` / ``nova_pruned_block_rows`` / ``nova_merge_cache_rows``) with the row pitch
+N, and each block's per-image cache lengths are kept in a device array that the block call itself
+advances.  Nothing on that path synchronises with the host.
 """
 from __future__ import annotations
 
@@ -31,7 +33,8 @@ from .binding import NOVA_BF16, NOVA_F32, BlockShape, BlockVariant, Nova
 class ScaleResult:
     """What one scale produced (device tensors are views of the runner's buffers of that scale)."""
     out: torch.Tensor                     # [B, N, C] output of the last block
-    k: List[int]                          # keep count used by every block
+    k: List[object]                       # per block: the keep count (int), or in controller mode a [B] int32
+                                          # device tensor with every image's own count
     mean_entropy: Optional[torch.Tensor]  # [B] scale mean entropy of the last block's logits, if logits were given
     block_out: List[torch.Tensor]         # per block [B, N, C] (kept for inspection)
     block_cache: List[torch.Tensor]       # per block residual cache [B, N, C]
@@ -86,12 +89,17 @@ class ImageRunner:
         self._state = torch.zeros(B, dtype=torch.float32, device=device)      # layer-ratio running sums
         self._ratio_tj = torch.empty(B, dtype=torch.float32, device=device)
         self._k_row = torch.empty(B, dtype=torch.int32, device=device)
+        # per-image cache lengths of every block (device): exact once images keep different numbers of tokens;
+        # kv_len then holds the host's upper bound
+        self.kv_rows = [torch.zeros(B, dtype=torch.int32, device=device) for _ in range(self.L)]
 
     def reset(self):
         """Forget the previous image: cache lengths back to zero, no residual cache (buffers are reused)."""
         self.kv_len = [0] * self.L
         self.cache = [None] * self.L
         self.cache_grid = None
+        for t in self.kv_rows:
+            t.zero_()
 
     def _shape(self, N: int, j: int, k: int) -> BlockShape:
         return BlockShape(self.code, self.B, N, self.C, self.heads, self.kv_len[j], self.cap, k, self.ffn_mult)
@@ -210,6 +218,7 @@ class ImageRunner:
         idxs: List[torch.Tensor] = []
         have_mean = False
         for j in range(self.L):
+            k_rows = None                             # per-image counts of this block (device), controller mode only
             if dense:
                 k = N
                 if logits is not None and j == self.L - 1:
@@ -219,27 +228,33 @@ class ImageRunner:
                 n.entropy(logits[j], H, mean)
                 have_mean = True
                 if ratio_t is not None:
+                    # per-image counts, on the device from here to the merge: row pitch N
                     n.layer_ratio(mean, self._state, ratio_t, j + 1, N, self._ratio_tj, self._k_row)
-                    k = int(self._k_row.max().item())           # one host read per block (see module text)
+                    k, k_rows = N, self._k_row
                 else:
-                    k = int(k_table[j])
-                n.select(H, k, idx, mask)
+                    k, k_rows = int(k_table[j]), None
+                n.select(H, k, idx, mask, k_per_row=k_rows)
             shape = self._shape(N, j, k)
             self._ensure_workspace(shape)
             y = torch.empty((B, max(k, 1), C), dtype=self.dtype, device=dev)
             out = torch.empty((B, N, C), dtype=self.dtype, device=dev)
             cache_new = torch.empty((B, N, C), dtype=self.dtype, device=dev) if keep_cache else None
-            n.pruned_block_variant(shape, self.weights[j], self.variants[j], x, idx, self.k_cache[j], self.v_cache[j],
-                                   y, self._workspace)
+            # the block reads and advances the per-image cache lengths (equal to kv_len as long as every image
+            # has kept the same number of tokens)
+            n.pruned_block_rows(shape, self.weights[j], self.variants[j], k_rows, self.kv_rows[j], self.kv_rows[j], x,
+                                idx, self.k_cache[j], self.v_cache[j], y, self._workspace)
             pg = self.cache_grid if self.cache[j] is not None else g
-            n.merge_cache_interp(self.interp, g, g, pg, pg, k, x, y, idx, mask, self.cache[j], out, cache_new)
+            if k_rows is None:
+                n.merge_cache_interp(self.interp, g, g, pg, pg, k, x, y, idx, mask, self.cache[j], out, cache_new)
+            else:
+                n.merge_cache_rows(self.interp, g, g, pg, pg, k, k_rows, x, y, idx, mask, self.cache[j], out, cache_new)
             self.kv_len[j] += k
             if inspect:
                 ents.append(H.clone())
                 idxs.append(idx.flatten()[:B * k].view(B, k).clone())
             if keep_cache:
                 self.cache[j] = cache_new
-            ks.append(k)
+            ks.append(k if k_rows is None else k_rows.clone())
             outs.append(out)
             caches.append(cache_new)
             x = out

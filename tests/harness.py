@@ -179,3 +179,84 @@ def check_block(hb: HostBlock, tol: float, rows=None, poison: bool = True) -> Di
     assert torch.equal(unpack_k_rows(st.k_cache, 0, P).cpu(), hb.k_prior), "prior key rows were modified"
     assert torch.equal(unpack_v_rows(st.v_cache, 0, P).cpu(), hb.v_prior), "prior value rows were modified"
     return errs
+
+
+def check_block_rows(hb: HostBlock, k_rows, kv_rows, tol: float, kpitch: Optional[int] = None) -> Dict[str, float]:
+    """One block with per-image keep counts and per-image cache lengths on the device (nova_select with
+    per-row counts -> nova_pruned_block_rows -> nova_merge_cache_rows) against the oracle's per-image form.
+    Image b keeps k_rows[b] tokens and holds kv_rows[b] <= P prior rows; the row pitch defaults to N.  Cache rows
+    the call must neither read nor write are NaN and must still be NaN afterwards."""
+    wl, s = hb.wl, hb.scale
+    B, N, C, P = wl.B, s.N, wl.C, s.kv_len
+    kpitch = N if kpitch is None else kpitch
+    assert len(k_rows) == B and len(kv_rows) == B and max(k_rows) <= kpitch and max(kv_rows) <= P
+    dev = "cuda"
+    n = nova()
+    tdt = WL.torch_dtype(wl.dtype)
+    cap = wl.kv_capacity(s)
+    nan = float("nan")
+    kc = pack_k_cache(hb.k_prior.to(dev), wl.heads, cap, nan)
+    vc = pack_v_cache(hb.v_prior.to(dev), wl.heads, cap, nan)
+    for b in range(B):                                   # rows past an image's own prior rows are not its cache
+        kc[b, :, kv_rows[b]:] = nan
+        vc[b, :, :, kv_rows[b]:] = nan
+    kc0, vc0 = kc.clone(), vc.clone()
+    x, logits = hb.x.to(dev), hb.logits.to(dev)
+    W = {name: t.to(dev) for name, t in hb.weights.items()}
+    H = torch.empty((B, N), dtype=torch.float32, device=dev)
+    idx = torch.full((B, kpitch), -7, dtype=torch.int32, device=dev)
+    mask = torch.full((B, N), 9, dtype=torch.uint8, device=dev)
+    y = torch.full((B, kpitch, C), nan, dtype=tdt, device=dev)
+    out = torch.full((B, N, C), nan, dtype=tdt, device=dev)
+    cn = torch.full((B, N, C), nan, dtype=tdt, device=dev)
+    kd = torch.tensor(k_rows, dtype=torch.int32, device=dev)
+    kvd = torch.tensor(kv_rows, dtype=torch.int32, device=dev)
+    kv_next = torch.full((B,), -1, dtype=torch.int32, device=dev)
+    from paper_2602_01345_amd import BlockShape, NOVA_BF16, NOVA_F32
+    shape = BlockShape(NOVA_BF16 if wl.dtype == "bf16" else NOVA_F32, B, N, C, wl.heads, P, cap, kpitch, wl.ffn_mult)
+    ws = torch.empty(max(n.workspace_bytes(shape), 256), dtype=torch.uint8, device=dev)
+    ws.view(torch.int16).fill_(0x7fc0)                   # NaN bit patterns (bf16; fp32 pairs too): stale workspace must not leak
+    n.entropy(logits, H)
+    n.select(H, kpitch, idx, mask, k_per_row=kd)
+    n.pruned_block_rows(shape, W, None, kd, kvd, kv_next, x, idx, kc, vc, y, ws)
+    n.merge_cache_rows(0, s.grid, s.grid, s.prev_grid, s.prev_grid, kpitch, kd, x, y, idx, mask,
+                       hb.cache_prev.to(dev), out, cn)
+    torch.cuda.synchronize()
+
+    H_gpu = H.cpu().numpy()
+    assert entropy_ok(H_gpu, O.entropy(f64(hb.logits)))
+    ridx, rmask = O.select(H_gpu, list(k_rows))
+    assert np.array_equal(mask.cpu().numpy(), rmask), "keep mask differs"
+    kmax = ridx.shape[1]
+    got_idx = idx.cpu().numpy()
+    assert np.array_equal(got_idx[:, :kmax], ridx) and np.all(got_idx[:, kmax:] == -1), "kept index lists differ"
+    assert kv_next.cpu().tolist() == [p + k for p, k in zip(kv_rows, k_rows)]
+    full_idx = np.full((B, kpitch), -1, dtype=np.int64)
+    full_idx[:, :kmax] = ridx
+    Wd = {name: f64(t) for name, t in hb.weights.items()}
+    ry, rk, rv = O.pruned_block(f64(hb.x), full_idx, Wd, f64(hb.k_prior), f64(hb.v_prior), wl.heads, kv_rows=kv_rows)
+    rout, rcn = O.merge_cache(f64(hb.x), ry, full_idx, f64(hb.cache_prev), s.prev_grid, s.prev_grid, s.grid, s.grid)
+    errs = {"out": nerr(out, rout), "cache_new": nerr(cn, rcn, scale_ref=rout)}
+    y_scale = max(float(np.max(np.abs(ry))), 1e-30)
+    k_scale = max(float(np.max(np.abs(rk))), 1e-30)
+    v_scale = max(float(np.max(np.abs(rv))), 1e-30)
+    ey = ek = ev = 0.0
+    for b in range(B):
+        k, Pb = k_rows[b], kv_rows[b]
+        if k:
+            ey = max(ey, float(np.max(np.abs(f64(y[b, :k]) - ry[b, :k]))) / y_scale)
+            ek = max(ek, float(np.max(np.abs(f64(unpack_k_rows(kc, Pb, Pb + k)[b]) - rk[b, :k]))) / k_scale)
+            ev = max(ev, float(np.max(np.abs(f64(unpack_v_rows(vc, Pb, Pb + k)[b]) - rv[b, :k]))) / v_scale)
+        # everything outside [Pb, Pb + k) is bit for bit what it was (NaN poison included)
+        for cache, before, dim in ((kc, kc0, 1), (vc, vc0, 2)):
+            ibits = torch.int16 if cache.element_size() == 2 else torch.int32      # compare bit patterns (NaN poison)
+            a, z = cache[b].view(ibits), before[b].view(ibits)
+            sl_lo = [slice(None)] * 3
+            sl_hi = [slice(None)] * 3
+            sl_lo[dim], sl_hi[dim] = slice(0, Pb), slice(Pb + k, None)
+            assert torch.equal(a[tuple(sl_lo)], z[tuple(sl_lo)]) and torch.equal(a[tuple(sl_hi)], z[tuple(sl_hi)]), \
+                f"image {b}: cache rows outside its appended range were modified"
+    errs.update(y_kept=ey, k_new=ek, v_new=ev)
+    for name, e in errs.items():
+        assert e <= tol, f"{name}: normalised max error {e:.3e} > {tol:.1e}"
+    return errs
