@@ -126,6 +126,57 @@ def cpu_baseline(hb0, wl, scale, ks):
                       f"entropy+select+pruned block+merge in float64 NumPy, {dt:.1f} s"}
 
 
+def compact_config(nova, wl, scale, steps=3, warmup=2, reps=2):
+    """One workload scale, measured compactly: ms per step (all L blocks, one stream) and, from an instrumented
+    pass, the fraction of the bf16 MFMA peak of attention and of the four projections together and the fraction of
+    the HBM peak of entropy and merge.  Inputs are drawn on the device; everything is freed on return."""
+    import torch
+    import workloads as WL
+    from paper_2602_01345_amd.binding import STAGES
+    from paper_2602_01345_amd.step import StepRunner
+    dtype = WL.torch_dtype(wl.dtype)
+    cap = wl.kv_capacity(scale)
+    runner = StepRunner(nova, B=wl.B, grid=scale.grid, prev_grid=scale.prev_grid, C=wl.C, heads=wl.heads,
+                        kv_len=scale.kv_len, kv_capacity=cap, dtype=dtype, ffn_mult=wl.ffn_mult)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(wl.seed + scale.grid)
+    ks = wl.k_table(scale)
+    for j in range(wl.L):
+        runner.add_block(device_block(wl, scale, j, ks[j], gen, dtype, cap))
+    x = torch.randn((wl.B, scale.N, wl.C), generator=gen, device="cuda").to(dtype)
+    for _ in range(warmup):
+        runner.run_step(x)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        runner.run_step(x)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    nova.profile_stages(range(len(STAGES)))
+    for _ in range(reps):
+        runner.run_step(x)
+    torch.cuda.synchronize()
+    nova.profile_stages([])
+    work = [stage_work(wl, scale, k) for k in ks]
+    t = {}
+    for si, name in enumerate(STAGES):
+        t[name], _ = nova.profile_collect(si)
+    tot = lambda name: sum(w[name][1] for w in work) * reps
+    gemms = ("qkv", "oproj", "ffn1", "ffn2")
+    kept = wl.B * sum(ks)
+    res = {"grid": scale.grid, "kv_len": scale.kv_len, "kept_tokens_per_step": kept, "ms_per_step": round(ms, 3),
+           "kept_tokens_per_s": round(kept / (ms * 1e-3)),
+           "attention_frac_mfma_peak": round(tot("attention") / (t["attention"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+           "gemm_frac_mfma_peak": round(sum(tot(g) for g in gemms) / (sum(t[g] for g in gemms) * 1e-3) / 1e12
+                                        / MFMA_BF16_PEAK_TFLOPS, 4),
+           "entropy_frac_hbm_peak": round(tot("entropy") / (t["entropy"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+           "merge_frac_hbm_peak": round(tot("merge") / (t["merge"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+           "stage_ms_per_step": {n: round(v / reps, 3) for n, v in t.items()}}
+    del runner, x
+    torch.cuda.empty_cache()
+    return res
+
+
 def image_chain(nova, wl, weights, gen):
     """All scales of the workload's grid list for one batch of images: dense up to the scale before the
     first pruned one (which also builds the residual caches), then the pruned scales with the workload's
@@ -254,9 +305,11 @@ def main():
     ap.add_argument("--overlap", action="store_true",
                     help="run entropy + selection of the next block on a second stream next to the current block's "
                          "gather and QKV projection (default: every kernel on one stream)")
-    ap.add_argument("--image", action="store_true",
-                    help="also time the chained multi-scale run (all scales of the config's grid list) and "
-                         "report ms per image")
+    ap.add_argument("--no-image", action="store_true",
+                    help="skip the chained multi-scale run (all scales of the config's grid list, ms per image)")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the compact measurements of the other workloads' last scales and of this workload's "
+                         "earlier pruned scales")
     ap.add_argument("--variants", action="store_true",
                     help="also time the step with the block variants on (modulation and gates, unit-length q/k, "
                          "tanh GELU, a cross-attention sub-layer over 77 condition tokens) and the other "
@@ -384,6 +437,13 @@ def main():
             work = keep
             del f32, Hs
         sustained("select", lambda: [nova.select(st.entropy, st.k, st.kept_idx, st.keep_mask) for st in blocks])
+        # entropy and selection as the step issues them, one after the other per block: the pair's rate over the
+        # bytes of both (selection alone is latency: tens of kilobytes per launch)
+        for w in work:
+            w["entropy_select_pair"] = ("bytes", w["entropy"][1] + w["select"][1])
+        sustained("entropy_select_pair", lambda: [(nova.entropy(st.logits, st.entropy),
+                                                   nova.select(st.entropy, st.k, st.kept_idx, st.keep_mask))
+                                                  for st in blocks])
         sustained("merge", lambda: [nova.merge_cache(scale.grid, scale.grid, scale.prev_grid, scale.prev_grid, st.k, x,
                                                      st.y_kept, st.kept_idx, st.keep_mask, st.cache_prev, st.out,
                                                      st.cache_new) for st in blocks])
@@ -425,6 +485,29 @@ def main():
                                    "frac_mfma_peak": round(hfl / (hus * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                                    "bound": "mfma", "logits_bytes_not_written": wl.B * scale.N * wl.V * 2}
             del hh, hw, hH, hws
+
+    # The attention kernel's time depends mildly on the scores (its softmax reference point moves only when a score
+    # lies far above it): the workload's weights give near-uniform scores, the favourable case.  The same step with
+    # the query projections scaled up 16-fold (scores tens of nats wide, peaked attention) is timed for comparison.
+    wide = None
+    if not args.no_stage_pass and wl.dtype == "bf16":
+        C = wl.C
+        for st in runner.blocks:
+            st.weights["w_qkv"][:C] *= 16.0
+            st.weights["b_qkv"][:C] *= 16.0
+        nova.profile_stages([dom])
+        for _ in range(2):
+            runner.run_step(x)
+        torch.cuda.synchronize()
+        nova.profile_stages([])
+        w_ms, w_n = nova.profile_collect(dom)
+        for st in runner.blocks:
+            st.weights["w_qkv"][:C] /= 16.0            # powers of two: the bf16 weights come back bit for bit
+            st.weights["b_qkv"][:C] /= 16.0
+        w_avg_s = w_ms / max(w_n, 1) * 1e-3
+        wide = {"achieved": dom_flops / w_avg_s / 1e12, "avg_launch_us": w_avg_s * 1e6,
+                "frac": dom_flops / w_avg_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                "note": "query projection scaled 16-fold: scores tens of nats wide, the softmax reference moves often"}
 
     # what the chip sustains for plain kernels (published peaks: HBM 8 TB/s, dense bf16 MFMA 2.5 PFLOP/s)
     peaks = {}
@@ -469,15 +552,28 @@ def main():
         "roofline": {"kernel": f"attention_bf16_kernel<{wl.dh},...> (+ its split-merge pass)", "bound": "mfma",
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic, "launches": dom_n,
-                     "avg_launch_us": dom_avg_s * 1e6, "flops_per_launch": dom_flops},
+                     "avg_launch_us": dom_avg_s * 1e6, "flops_per_launch": dom_flops,
+                     "scores": "near-uniform (weights N(0, 0.02^2)): the favourable case for the lazy softmax reference",
+                     "frac_wide_scores": None if wide is None else wide["frac"], "wide_scores": wide},
         "kernels": kernels,
         "hbm_kernels_sustained": hbm,
         "achievable_peaks": peaks,
     }
-    if args.image:
-        out["image_chain"] = image_chain(nova, wl, [st.weights for st in runner.blocks], gen)
     if args.variants:
         out["variant_step"] = variant_step(nova, runner, wl, x, gen, dtype, args.steps)
+    if not args.no_image and not args.no_stage_pass:
+        out["image_chain"] = image_chain(nova, wl, [st.weights for st in runner.blocks], gen)
+    if not args.no_other_configs and not args.no_stage_pass and args.config == "cfg5":
+        # the other workloads' last scales and this workload's earlier pruned scales, a few steps each
+        del runner, x
+        torch.cuda.empty_cache()
+        other = {}
+        for name in ("cfg2", "cfg3", "cfg4"):
+            w2 = WL.WORKLOADS[name]
+            other[name] = compact_config(nova, w2, w2.last)
+        for sc in wl.scales[:-1]:
+            other[f"cfg5@{sc.grid}x{sc.grid}"] = compact_config(nova, wl, sc)
+        out["other_configs"] = other
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(hb0, wl, scale, ks)
     print(json.dumps(out))

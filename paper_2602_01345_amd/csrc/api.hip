@@ -1,5 +1,6 @@
 // C ABI of the library (declared in include/nova.h): argument checks on the host,
 // then dispatch to the kernel launchers.  No allocation, no synchronisation.
+#include <algorithm>
 #include <cstdlib>
 #include <new>
 
@@ -52,13 +53,20 @@ BlockWorkspace carve_workspace(const nova_block_shape& s, void* base) {
   w.x1 = p + off;   off += up256(M * C * e);
   w.hid = p + off;  off += up256(M * F * e);
   w.part_o = w.part_ml = nullptr;
+  w.part_floats = 0;
   if (s.dtype == NOVA_BF16) {
-    // split-key attention partials: attention_max_split() partial results per item (batch row, head, query
-    // block), each a whole query block (at most 256 queries) of dh floats plus (max, sum) per query
-    const size_t ns = (size_t)attention_max_split();
+    // One region serves two users, one after the other: the partial results of the attention items that are cut
+    // into key runs (only the items of the last, partly filled round over the workgroup slots are: at most
+    // kAttentionMaxPieces runs of up to 256 queries x dh floats, or attention_max_split() per item when the call
+    // is small), and the fp32 K-slice sums of the projections back to C (slices x rows x C for launches whose tiles
+    // fill at most half of the compute units: at most 128 tiles of 256 x 256).
+    const size_t dh = (size_t)(s.C / s.heads);
     const size_t Mp = (size_t)s.B * (((size_t)s.k + 255) / 256 * 256);
-    w.part_o = p + off;  off += up256(ns * Mp * C * 4);
-    w.part_ml = p + off; off += up256(ns * Mp * (size_t)s.heads * 2 * 4);
+    const size_t attn = std::min((size_t)attention_max_split() * Mp * C, (size_t)kAttentionMaxPieces * 256 * dh);
+    const size_t kslice = std::min((size_t)4 * M * C, (size_t)128 * 256 * 256);
+    w.part_floats = (int64_t)std::max(attn, kslice);
+    w.part_o = p + off;  off += up256((size_t)w.part_floats * 4);
+    w.part_ml = p + off; off += up256((size_t)w.part_floats / dh * 2 * 4);     // (reference, sum) per query and run
   }
   w.total = off;
   return w;

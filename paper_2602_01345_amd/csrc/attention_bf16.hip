@@ -516,7 +516,8 @@ __global__ __launch_bounds__(kCombineRows * (DH / 4)) void attention_combine_ker
 template <int DH, int NQ, int NST, int OCC, int NW>
 hipError_t launch_cfg(const nova_ctx* ctx, hipStream_t st, const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int B,
                       int k, int C, int heads, int cap, int kv_total, bf16_t* out, float* part_o,
-                      float* part_ml, const int32_t* k_rows, const int32_t* kv_rows, int P, int self_keys) {
+                      float* part_ml, int64_t part_floats, const int32_t* k_rows, const int32_t* kv_rows, int P,
+                      int self_keys) {
   constexpr int BQ = NW * NQ * 32;
   const int nqb = (k + BQ - 1) / BQ;
   const int items = nqb * heads * B;                      // (batch row, head, query block)
@@ -531,14 +532,14 @@ hipError_t launch_cfg(const nova_ctx* ctx, hipStream_t st, const bf16_t* q, cons
   //   (ii)  every item cut into s runs;
   //   (iii) two resident workgroups per CU only: one uncut item per CU first, the others cut into s runs that
   //         fill the second slots (and leave the uncut workgroup alone on its CU once they are done).
-  // The partial workspace holds kMaxSplit * items partials of BQ * DH floats.
+  // The partial workspace holds part_floats / (BQ * DH) partial results.
   constexpr float kSolo = 1.8f;
   int n_whole = items, nsplit = 1;
   if (part_o && part_ml) {
     const int cus = slots / OCC;
     const int rest = items % slots;                       // items of the last round (0: nothing to cut)
     auto usable = [&](int s, int cut) {                   // every run owns at least one tile; partials fit
-      return s >= 1 && (s - 1) * ((ntiles + s - 1) / s) < ntiles && (int64_t)cut * s <= (int64_t)kMaxSplit * items;
+      return s >= 1 && (s - 1) * ((ntiles + s - 1) / s) < ntiles && (int64_t)cut * s * BQ * DH <= part_floats;
     };
     if (rest > 0) {
       float best = rest <= cus ? 1.0f / kSolo : 1.0f;     // (i)
@@ -578,8 +579,8 @@ int attention_max_split() { return kMaxSplit; }
 
 hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void* qv, const void* kcv,
                                  const void* vcv, int B, int k, int C, int heads, int cap, int kv_total,
-                                 void* outv, float* part_o, float* part_ml, const int32_t* k_rows,
-                                 const int32_t* kv_rows, int P, int self_keys) {
+                                 void* outv, float* part_o, float* part_ml, int64_t part_floats,
+                                 const int32_t* k_rows, const int32_t* kv_rows, int P, int self_keys) {
   const bf16_t* q = static_cast<const bf16_t*>(qv);
   const bf16_t* kc = static_cast<const bf16_t*>(kcv);
   const bf16_t* vc = static_cast<const bf16_t*>(vcv);
@@ -594,7 +595,7 @@ hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void
   if (nq < 1 || nq > 4) nq = 1;
 #define ATT_LAUNCH(DH_, NQ_, NST_, OCC_, NW_)                                                                       \
   return launch_cfg<DH_, NQ_, NST_, OCC_, NW_>(ctx, st, q, kc, vc, B, k, C, heads, cap, kv_total, out, \
-                                               part_o, part_ml, k_rows, kv_rows, P, self_keys)
+                                               part_o, part_ml, part_floats, k_rows, kv_rows, P, self_keys)
   if (dh == 64) {
     if (nq == 1) ATT_LAUNCH(64, 1, 2, 2, 4);
     if (nq == 4) ATT_LAUNCH(64, 1, 2, 3, 4);

@@ -46,6 +46,7 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
   ep.k_rows = rc.k_rows; ep.kv_rows = rc.kv_rows;
   ep.gate_pitch = ada_pitch;
   ep.part = reinterpret_cast<float*>(ws.part_o);          // free once attention is done: K-slice sums of the projections back to C
+  ep.part_floats = ws.part_floats;
 
   // the attention kernel takes its query rows multiplied by (score scale * log2 e); unit-length queries get the
   // factor when they are rescaled (a factor before that would cancel)
@@ -63,8 +64,8 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
   {
     StageTimer t(ctx, st, NOVA_STAGE_ATTENTION);
     e = launch_attention_bf16(ctx, st, q, kc, vc, s.B, s.k, C, s.heads, s.kv_capacity, s.kv_len + s.k, attn,
-                              reinterpret_cast<float*>(ws.part_o), reinterpret_cast<float*>(ws.part_ml), rc.k_rows,
-                              rc.kv_rows, s.kv_len, 1);
+                              reinterpret_cast<float*>(ws.part_o), reinterpret_cast<float*>(ws.part_ml), ws.part_floats,
+                              rc.k_rows, rc.kv_rows, s.kv_len, 1);
   }
   if (e != hipSuccess) return e;
 
@@ -86,7 +87,7 @@ hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_sha
     if (e != hipSuccess) return e;
     e = launch_attention_bf16(ctx, st, q, var.k_text, var.v_text, s.B, s.k, C, s.heads, var.text_capacity,
                               var.text_len, attn, reinterpret_cast<float*>(ws.part_o),
-                              reinterpret_cast<float*>(ws.part_ml), rc.k_rows, nullptr, 0, 0);
+                              reinterpret_cast<float*>(ws.part_ml), ws.part_floats, rc.k_rows, nullptr, 0, 0);
     if (e != hipSuccess) return e;
     ep.bias = static_cast<const bf16_t*>(var.b_co); ep.out = x1; ep.ldo = C; ep.res = x1;
     e = launch_gemm_bf16(ctx, st, EPI_RESIDUAL, attn, var.w_co, M, C, C, ep);

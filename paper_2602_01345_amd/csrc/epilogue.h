@@ -42,8 +42,10 @@ struct EpiParams {
   // bf16 kernels: factor on the query features (EPI_QKV: columns < C; EPI_PLAIN: all) before they are rounded --
   // the attention kernel wants its queries multiplied by (score scale * log2 e)
   float q_scale;
-  // K slicing (few rows, long K): fp32 scratch for [slices][M][Nout] partial sums, or nullptr to forbid slicing
+  // K slicing (few rows, long K): fp32 scratch for [slices][rows of the launch][Nout] partial sums (part_floats
+  // floats), or nullptr to forbid slicing
   float* part;
+  int64_t part_floats;
 };
 
 // Exact-form GELU 0.5 v (1 + erf(v / sqrt 2)).  erf through the rational approximation 7.1.26 of

@@ -297,7 +297,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
   // The MFMAs ran with the weight rows as the A operand, so a lane owns token l % 32 of each MFMA
   // tile and, per register group r / 4, four consecutive output features.
   if constexpr (MODE == EPI_PARTIAL) {
-    float* pp = ep.part + (int64_t)kslice * M * Nout;
+    float* pp = ep.part + ((int64_t)kslice * (M - m_base) - m_base) * Nout;     // [slice][row - m_base][Nout]
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       const int row = m0 + wm * (BM / WM) + i * 32 + r32;
@@ -532,7 +532,7 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float* __restric
   const int row = m_base + (int)(v / cpr), col = (int)(v % cpr) * 8;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int s = 0; s < kslices; ++s) {
-    const float* p = part + ((int64_t)s * M + row) * Nout + col;
+    const float* p = part + ((int64_t)s * (M - m_base) + row - m_base) * Nout + col;
     const f32x4 a = *reinterpret_cast<const f32x4*>(p), b = *reinterpret_cast<const f32x4*>(p + 4);
 #pragma unroll
     for (int e = 0; e < 4; ++e) { acc[e] += a[e]; acc[4 + e] += b[e]; }
@@ -675,7 +675,8 @@ hipError_t launch_part(hipStream_t st, int cfg, const bf16_t* A, const bf16_t* W
       int ks = 1;
       if (ksplit > 0) ks = ksplit;
       else while (ks < 4 && tiles * ks * 2 <= cus) ks *= 2;
-      if ((ks == 2 || ks == 4) && K % (ks * bk) == 0 && K / (ks * bk) >= 16) {
+      if ((ks == 2 || ks == 4) && K % (ks * bk) == 0 && K / (ks * bk) >= 16 &&
+          (int64_t)ks * (M - m_base) * Nout <= ep.part_floats) {
         hipError_t e;
         if (cfg == 2) e = launch_cfg<256, 128, 4, 2, 64, 3, false, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, 0, ks);
         else if (cfg == 5) e = launch_cfg<128, 128, 2, 4, 64, 3, false, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, 0, ks);
@@ -692,7 +693,8 @@ hipError_t launch_part(hipStream_t st, int cfg, const bf16_t* A, const bf16_t* W
     // tile column is one workgroup, too few to stream the weights at speed.  K is cut into slices summed by more
     // workgroups (at least eight K steps per slice); a second small pass adds the slices and applies the epilogue.
     const int wgs = ((M - m_base + (cfg == 3 ? 63 : 127)) / (cfg == 3 ? 64 : 128)) * ((Nout + 31) / 32);
-    if ((cfg == 3 || cfg == 4) && ep.part && wgs <= 128 && K >= 2048 && K % (4 * 64) == 0 && Nout % 8 == 0) {
+    if ((cfg == 3 || cfg == 4) && ep.part && wgs <= 128 && K >= 2048 && K % (4 * 64) == 0 && Nout % 8 == 0 &&
+        (int64_t)4 * (M - m_base) * Nout <= ep.part_floats) {
       const int ks = 4;
       const hipError_t e =
           cfg == 3 ? launch_cfg<64, 32, 2, 1, 64, 6, true, EPI_PARTIAL>(st, A, W, m_base, M, Nout, K, ep, 0, ks)

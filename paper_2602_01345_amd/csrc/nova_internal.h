@@ -79,6 +79,7 @@ struct BlockWorkspace {
   char* hid;   // [M, F]  FFN hidden
   char* part_o;   // bf16 path: attention partial sums, fp32: max_split per item, [query block][dh] each
   char* part_ml;  // bf16 path: their softmax reference point (log2 units) and sum per query
+  int64_t part_floats;   // capacity of part_o in floats (part_ml holds 2 floats per dh of them)
   size_t total;
 };
 BlockWorkspace carve_workspace(const nova_block_shape& s, void* base);
@@ -127,16 +128,17 @@ size_t head_entropy_partial_bytes(const nova_ctx* ctx, int M, int V, int C);
 // attention_bf16.hip: attn[B*k, C] = softmax(ln 2 * q K^T) V per head over kv_total cached keys: the query rows
 // arrive multiplied by (score scale * log2 e) -- kAttnLog2e times the scale of the scores -- by whoever wrote
 // them (the projection's epilogue or the unit-length rescaling), so the kernel's scores are in log2 units
-// part_o / part_ml: workspace for split-key partial results (max_split * B * roundup(k, 256) * C and
-// ... * heads * 2 floats), or nullptr to forbid splitting
+// part_o / part_ml: workspace for split-key partial results (part_floats floats, and 2 floats per dh of them),
+// or nullptr to forbid splitting
 int attention_max_split();
+constexpr int kAttentionMaxPieces = 512;      // key runs of cut attention items per launch the workspace has room for
 constexpr float kAttnLog2e = 1.4426950408889634f;
 // k_rows / kv_rows (device, or nullptr): per-image keep counts and prior-row counts.  Image b's live queries are
 // slots [0, k_rows[b]) of its k-slot segment (the other slots get zeros); with self_keys its keys are its own
 // kv_rows[b] (default P) prior rows plus its own kept rows, otherwise kv_total keys for every image.
 hipError_t launch_attention_bf16(const nova_ctx* ctx, hipStream_t st, const void* q, const void* kc, const void* vc,
                                  int B, int k, int C, int heads, int cap, int kv_total, void* out,
-                                 float* part_o, float* part_ml, const int32_t* k_rows = nullptr,
+                                 float* part_o, float* part_ml, int64_t part_floats, const int32_t* k_rows = nullptr,
                                  const int32_t* kv_rows = nullptr, int P = 0, int self_keys = 1);
 // block_bf16.hip: MFMA path
 hipError_t launch_block_bf16(nova_ctx* ctx, hipStream_t st, const nova_block_shape& s,
