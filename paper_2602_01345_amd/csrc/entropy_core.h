@@ -16,6 +16,49 @@ constexpr float kClamp = -200.0f;   // e^-200 == 0 in fp32; keeps (m - x) * e fi
 constexpr float kClampNat = -140.0f; // likewise for the per-element path (natural units; 2^(-140 log2 e) flushes to 0)
 
 
+// Wave-wide sum / maximum on the DPP cross-lane paths of the vector ALU (quads, half rows, rows of 16, then the two
+// row broadcasts), read back from lane 63 as a wave-uniform scalar: six dependent vector instructions and no trip
+// through the LDS crossbar, which is what a butterfly of lane shuffles costs six times over.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_or(float v, float identity) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(identity), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+__device__ __forceinline__ float wave_sum_uniform(float v) {
+  v += dpp_or<0xB1, 0xF>(v, 0.0f);          // quad_perm [1,0,3,2]
+  v += dpp_or<0x4E, 0xF>(v, 0.0f);          // quad_perm [2,3,0,1]
+  v += dpp_or<0x141, 0xF>(v, 0.0f);         // row_half_mirror
+  v += dpp_or<0x140, 0xF>(v, 0.0f);         // row_mirror: every lane holds the sum of its row of 16
+  v += dpp_or<0x142, 0xA>(v, 0.0f);         // row_bcast15 into rows 1 and 3
+  v += dpp_or<0x143, 0xC>(v, 0.0f);         // row_bcast31 into rows 2 and 3: lane 63 holds the total
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+__device__ __forceinline__ float wave_max_uniform(float v) {
+  v = fmaxf(v, dpp_or<0xB1, 0xF>(v, -INFINITY));
+  v = fmaxf(v, dpp_or<0x4E, 0xF>(v, -INFINITY));
+  v = fmaxf(v, dpp_or<0x141, 0xF>(v, -INFINITY));
+  v = fmaxf(v, dpp_or<0x140, 0xF>(v, -INFINITY));
+  v = fmaxf(v, dpp_or<0x142, 0xA>(v, -INFINITY));
+  v = fmaxf(v, dpp_or<0x143, 0xC>(v, -INFINITY));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+// ln(1 + x) for x >= 0 to a few fp32 ulps, on the native log2 unit: a short alternating series where 1 + x would
+// round away most of x, else ln(u) with u = fl(1 + x) plus the first-order term for what that rounding dropped.
+__device__ __forceinline__ float log1p_pos(float x) {
+  if (x < 0.0625f) {
+    float p = fmaf(x, 1.0f / 7.0f, -1.0f / 6.0f);
+    p = fmaf(p, x, 1.0f / 5.0f);
+    p = fmaf(p, x, -1.0f / 4.0f);
+    p = fmaf(p, x, 1.0f / 3.0f);
+    p = fmaf(p, x, -1.0f / 2.0f);
+    p = fmaf(p, x, 1.0f);
+    return p * x;                              // next term x^8 / 8: below 2e-10 of the result
+  }
+  const float u = 1.0f + x;
+  const float lost = x - (u - 1.0f);
+  return fmaf(__builtin_amdgcn_logf(u), 0.6931471805599453f, lost * __builtin_amdgcn_rcpf(u));
+}
+
 struct Row {
   float m;        // running maximum, wave uniform (-inf before the first element)
   float R, T;     // per-lane partial sums against m, excluding elements equal to m
@@ -74,11 +117,11 @@ struct Row {
   }
 
   __device__ __forceinline__ float finish() const {
-    float Rw = wave_sum(R) + cS;
-    float Tw = wave_sum(T) + cT;
+    float Rw = wave_sum_uniform(R) + cS;
+    float Tw = wave_sum_uniform(T) + cT;
     // S = cnt + Rw, one maximum instance split off for log1p
     float extra = Rw + (float)(cnt - 1);
-    float H = log1pf(extra) + Tw / (1.0f + extra);
+    float H = log1p_pos(extra) + Tw * __builtin_amdgcn_rcpf(1.0f + extra);
     // empty or all -inf row, a +inf logit (inf - inf): undefined; NaN logit
     if (m == -INFINITY || m == INFINITY || cnt < 1 || nan) H = __builtin_nanf("");
     return (H < 0.0f) ? 0.0f : H;                             // NaN passes through
@@ -107,7 +150,7 @@ __device__ __forceinline__ void walk_rows(const T* __restrict__ logits, int64_t 
     for (int c = 0; c < CH; ++c)
 #pragma unroll
       for (int i = 0; i < VN; ++i) cm = fmaxf(cm, buf[c].get(i));
-    const float M = wave_max(cm);
+    const float M = wave_max_uniform(cm);
     st.rebase(M);
     const int before = st.cnt;
 #pragma unroll

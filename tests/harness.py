@@ -178,6 +178,11 @@ def check_block(hb: HostBlock, tol: float, rows=None, poison: bool = True) -> Di
     # prior cache rows must be untouched
     assert torch.equal(unpack_k_rows(st.k_cache, 0, P).cpu(), hb.k_prior), "prior key rows were modified"
     assert torch.equal(unpack_v_rows(st.v_cache, 0, P).cpu(), hb.v_prior), "prior value rows were modified"
+    if poison:
+        # and so must every slot behind the appended rows (NaN poison, in both cache layouts)
+        cap = wl.kv_capacity(s)
+        assert bool(torch.isnan(unpack_k_rows(st.k_cache, P + k, cap)).all()), "key slots behind the appended rows were written"
+        assert bool(torch.isnan(unpack_v_rows(st.v_cache, P + k, cap)).all()), "value slots behind the appended rows were written"
     return errs
 
 

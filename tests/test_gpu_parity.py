@@ -395,6 +395,23 @@ def test_block_bf16_with_every_tuning_knob(hx, knob, value, monkeypatch):
         _say(f"   C={C}: errors {errs}")
 
 
+@pytest.mark.parametrize("cfg", [None, "2", "6"])
+def test_block_bf16_value_append_at_every_alignment(hx, cfg, monkeypatch):
+    """The QKV projection's epilogue writes the value columns in 16-byte groups of eight cache slots: every offset of
+    the first appended slot inside such a group, keep counts that leave partial groups at both ends, an image boundary
+    inside a tile, and a feature count that puts query, key and value columns into one tile (C = 320 with 256- and
+    128-column tiles).  The harness also checks that no slot outside the appended range is written."""
+    from paper_2602_01345_amd import Nova
+    if cfg is not None:
+        monkeypatch.setenv("NOVA_GEMM_CFG", cfg)
+        monkeypatch.setattr(hx, "_NOVA", Nova(0))
+    _say(f"value append alignments, tile configuration {cfg}")
+    for P, k in ((64, 40), (65, 290), (66, 7), (67, 300), (132, 129), (133, 8), (134, 261), (135, 1)):
+        wl = _custom("bf16", B=2, grid=18, prev=12, P=P, C=320, heads=5)
+        errs = hx.check_block(hx.make_host_block(wl, 0, k=k), hx.BF16_TOL)
+        _say(f"   P={P} k={k}: errors {errs}")
+
+
 @pytest.mark.parametrize("ksplit", ["0", "2", "4", None])
 def test_block_bf16_ffn_down_projection_with_k_slices(hx, ksplit, monkeypatch):
     """The FFN down projection with large tiles and K = 4096 cut into 2 or 4 slices (fp32 partial sums, second
