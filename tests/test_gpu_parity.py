@@ -257,6 +257,18 @@ def test_cfg5_middle_blocks_ragged_last_rounds(hx, j):
     _say(f"   errors {errs}")
 
 
+@pytest.mark.parametrize("name,blocks,row", [("cfg5", (4, 8, 12, 16, 20, 24), 1), ("cfg4", (9, 18, 27), 6),
+                                             ("cfg3", (7, 15, 22), 9), ("cfg2", (3, 5, 8, 11, 13), 4)])
+def test_workload_blocks_in_between(hx, name, blocks, row):
+    """More blocks of every workload's last scale, one image each: the keep count (and with it every launch plan:
+    tile shapes, two-launch row plans, K slices, attention key runs) changes from block to block."""
+    wl = WL.WORKLOADS[name]
+    for j in blocks:
+        _say(f"{name} block {j} k={wl.k(j)} row {row}")
+        errs = hx.check_block(hx.make_host_block(wl, j), hx.BF16_TOL, rows=[row])
+        _say(f"   errors {errs}")
+
+
 @pytest.mark.parametrize("name,si,rows", [("cfg3", 0, [1]), ("cfg4", 0, [2]), ("cfg4", 1, [5]), ("cfg5", 0, [0]),
                                           ("cfg5", 1, [1]), ("cfg5", 2, [0])])
 def test_earlier_pruned_scales(hx, name, si, rows):
