@@ -448,6 +448,29 @@ def main():
                                                      st.y_kept, st.kept_idx, st.keep_mask, st.cache_prev, st.out,
                                                      st.cache_new) for st in blocks])
 
+        # the selector's own throughput, which B = 2 images cannot show: 4096 rows of 4096 entropies, half kept
+        # (one workgroup per row; read 4N, write 4k + N bytes per row)
+        sB, sN, sk = 4096, 4096, 2048
+        sH = torch.rand((sB, sN), generator=gen, device="cuda") * 8.0
+        sidx = torch.empty((sB, sk), dtype=torch.int32, device="cuda")
+        smask = torch.empty((sB, sN), dtype=torch.uint8, device="cuda")
+        for _ in range(2):
+            nova.select(sH, sk, sidx, smask)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            nova.select(sH, sk, sidx, smask)
+        e1.record()
+        torch.cuda.synchronize()
+        s_us = e0.elapsed_time(e1) * 1e3 / 5
+        s_bytes = sB * (4 * sN + 4 * sk + sN)
+        hbm["select_stress"] = {"shape": f"B={sB} rows of N={sN}, k={sk}", "us_per_launch": round(s_us, 1),
+                                "GB/s": round(s_bytes / (s_us * 1e-6) / 1e9, 1),
+                                "frac_hbm_peak": round(s_bytes / (s_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                                "rows_per_s": round(sB / (s_us * 1e-6))}
+        del sH, sidx, smask
+
         # the layer-linkage ratio kernel sits between entropy and select: a latency-bound launch
         # (B rows), reported as time per launch over one launch per block
         cm = torch.rand(wl.B, device="cuda") * 5.0 + 1.0
