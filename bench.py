@@ -88,9 +88,9 @@ def stage_work(wl, scale, k):
 
 
 def cpu_baseline(hb0, wl, scale, ks):
-    """Times the CPU oracle, as it stands, on three blocks of the step (first, middle, last: the most,
-    a typical and the fewest kept tokens), every batch row, one after the other: roughly 10 s of
-    float64 NumPy on the host cores.  Input generation is not timed."""
+    """Times the CPU oracle, as it stands, on four blocks of the step (first, two in between, last: from the most
+    to the fewest kept tokens), every batch row, one after the other: 10-15 s of float64 NumPy on the host
+    cores.  Input generation is not timed."""
     import numpy as np
     import workloads as WL
     from oracle import nova_oracle as O
@@ -100,7 +100,7 @@ def cpu_baseline(hb0, wl, scale, ks):
     except Exception:
         cores = os.cpu_count() or 1
     torch = __import__("torch")
-    blocks = sorted({0, wl.L // 2, wl.L - 1})
+    blocks = sorted({0, wl.L // 3, 2 * wl.L // 3, wl.L - 1})
     rows = min(wl.B, 4)
     dt, kept = 0.0, 0
     for j in blocks:
