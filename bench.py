@@ -553,7 +553,12 @@ def main():
         peaks["hbm_read_GBs"] = round(timed(lambda: nova.probe(0, big, None, 1, sink), 5) / 1e9, 1)
         peaks["hbm_copy_GBs"] = round(timed(lambda: nova.probe(1, big, big2, 1, sink), 5) / 1e9, 1)
         peaks["mfma_bf16_TFLOPs"] = round(timed(lambda: nova.probe(2, None, None, 2000, sink), 3) / 1e12, 1)
-        peaks["note"] = "plain kernels of this library (nova_probe): 1 GiB streaming read, 1 GiB copy (read+write bytes), MFMA-only loop"
+        rnd = torch.randn(16 << 20, generator=gen, device="cuda").to(torch.bfloat16)      # N(0,1) operands, 32 MiB
+        peaks["mfma_bf16_random_operands_TFLOPs"] = round(timed(lambda: nova.probe(3, rnd, None, 2000, sink), 3) / 1e12, 1)
+        del rnd
+        peaks["note"] = ("plain kernels of this library (nova_probe): 1 GiB streaming read, 1 GiB copy (read+write bytes), "
+                         "MFMA-only loop on constant register operands, and the same loop on N(0,1) operands (more bits "
+                         "switch per MFMA: more power, lower clock)")
         del big, big2
 
     traffic = None

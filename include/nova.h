@@ -374,10 +374,12 @@ int nova_profile_collect(nova_ctx* ctx, int stage, double* total_ms, int64_t* la
  * done by the launch.
  *   NOVA_PROBE_READ   streams `bytes` from src (16 bytes per lane, grid-stride)
  *   NOVA_PROBE_COPY   copies `bytes` from src to dst (work = 2 * bytes)
- *   NOVA_PROBE_MFMA   8 waves per CU, `iters` rounds of 32 independent bf16 32x32x16 MFMAs each
+ *   NOVA_PROBE_MFMA   8 waves per CU, `iters` rounds of 32 independent bf16 32x32x16 MFMAs each, constant operands
+ *   NOVA_PROBE_MFMA_DATA  the same loop on operands read once from src (at least CUs x 512 x 128 bytes of bf16
+ *                     values): what the matrix cores sustain depends on the data they are fed
  * src / dst: device, 16-byte aligned; sink: device fp32 [1] (never written in practice).
  */
-enum { NOVA_PROBE_READ = 0, NOVA_PROBE_COPY = 1, NOVA_PROBE_MFMA = 2 };
+enum { NOVA_PROBE_READ = 0, NOVA_PROBE_COPY = 1, NOVA_PROBE_MFMA = 2, NOVA_PROBE_MFMA_DATA = 3 };
 int nova_probe(nova_ctx* ctx, void* stream, int kind, const void* src, void* dst, int64_t bytes,
                int iters, float* sink, double* work);
 

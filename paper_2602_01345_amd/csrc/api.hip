@@ -141,6 +141,13 @@ int nova_probe(nova_ctx* ctx, void* stream, int kind, const void* src, void* dst
       // workgroups x waves x rounds x MFMAs x flops of one 32x32x16 MFMA
       *work = (double)ctx->num_cus * 8.0 * (double)iters * 32.0 * (2.0 * 32 * 32 * 16);
       break;
+    case NOVA_PROBE_MFMA_DATA:
+      // every lane reads 128 bytes of operands: num_cus workgroups of 512 lanes
+      if (iters < 1 || !src || reinterpret_cast<uintptr_t>(src) % 16 || bytes < (int64_t)ctx->num_cus * 512 * 128)
+        return NOVA_ERR_INVALID_ARG;
+      e = launch_probe_mfma_data(st, ctx->num_cus, src, iters, sink);
+      *work = (double)ctx->num_cus * 8.0 * (double)iters * 32.0 * (2.0 * 32 * 32 * 16);
+      break;
     default: return NOVA_ERR_INVALID_ARG;
   }
   return e == hipSuccess ? NOVA_OK : NOVA_ERR_HIP;

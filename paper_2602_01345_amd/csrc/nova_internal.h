@@ -61,6 +61,7 @@ hipError_t launch_layer_ratio(hipStream_t st, const float* mean_entropy, float* 
 hipError_t launch_probe_read(hipStream_t st, int num_cus, const void* src, int64_t bytes, float* sink);
 hipError_t launch_probe_copy(hipStream_t st, int num_cus, const void* src, void* dst, int64_t bytes);
 hipError_t launch_probe_mfma(hipStream_t st, int num_cus, int iters, float* sink);
+hipError_t launch_probe_mfma_data(hipStream_t st, int num_cus, const void* src, int iters, float* sink);
 hipError_t launch_entropy_bits(hipStream_t st, const void* logits, int dtype, int64_t rows_per_batch, int batch,
                                int d, float* H, float* mean);
 hipError_t launch_select(hipStream_t st, const float* H, int B, int N, int k, const int32_t* k_per_row,

@@ -330,7 +330,15 @@ def test_probe_kernels_report_their_work(hx):
     flops = nova.probe(2, None, None, 3, sink)
     torch.cuda.synchronize()
     assert torch.equal(src, dst) and float(sink) == 0.0
-    assert flops == torch.cuda.get_device_properties(0).multi_processor_count * 8 * 3 * 32 * 2 * 32 * 32 * 16
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert flops == cus * 8 * 3 * 32 * 2 * 32 * 32 * 16
+    # the same loop on operands read from memory: needs 128 bytes per lane of CUs x 512 lanes
+    data = torch.randn(cus * 512 * 64, device="cuda").to(torch.bfloat16)
+    assert nova.probe(3, data, None, 3, sink) == flops
+    with pytest.raises(Exception):
+        nova.probe(3, data[: data.numel() // 2], None, 3, sink)        # too few operands: rejected before the launch
+    torch.cuda.synchronize()
+    assert float(sink) == 0.0
 
 
 @pytest.mark.parametrize("P,k", [(0, 1), (0, 40), (3, 61), (64, 64), (127, 1), (500, 289)])
